@@ -1,0 +1,24 @@
+"""CPU oracle for the cached-prefix incremental-attention path.
+
+TEST INFRASTRUCTURE ONLY.  Nothing under this package is part of the product:
+only the test-suite, the smoke check and the benchmark's ``cpu_baseline`` leg
+may import it.  It shares no code, tables or helpers with the HIP path and is
+written directly from the paper's statement of the method.
+
+Pinned functions (see tests/test_oracle_*.py): page arithmetic, unpack, append,
+pack, attn_incremental, full_recompute.  No function here is "parity unpinned".
+"""
+from .mts_oracle import (  # noqa: F401
+    PagedStore,
+    pages_for,
+    store_bytes,
+    onload_pages,
+    kv_bytes_per_token,
+    attended_pairs,
+    decode_values,
+    unpack,
+    append,
+    pack,
+    attn_incremental,
+    full_recompute,
+)
