@@ -1,0 +1,183 @@
+/*
+ * mtserve.h - C ABI of the MI355X (gfx950) hot path of cross-request KV reuse for
+ * generative-recommendation serving: incremental-prefill attention over a paged GPU
+ * KV cache, and the kernels that move KV between the contiguous host layout and the
+ * paged GPU layout.
+ *
+ * The operations are the device half of the paper's seven-step workflow (Sec. 3.2):
+ *   step 3  Cache Scattering  -> mts_kv_unpack
+ *   step 4  Model Inference   -> mts_attn_incremental   (Sec. 2, Eq. 6-7; Alg. 1 step 8.4)
+ *   step 5  Cache Update      -> mts_kv_append          (Alg. 1 step 8.2)
+ *   step 6  Cache Offload     -> mts_kv_pack            (gather kernel of Sec. 4.2)
+ * Page allocation, LRU and the host chunk store are the caller's business (the paper's
+ * KVCacheManager, Sec. 3.1); this library consumes the page table it produces.
+ *
+ * General rules
+ *   - Every function returns an int32 status (MTS_OK = 0, errors < 0) unless stated.
+ *     Nothing throws, aborts, allocates, frees, or synchronises the host.
+ *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) of the CURRENT device.  Pointers marked "device" must be valid on
+ *     that device until the enqueued work has finished.  The caller owns every buffer.
+ *   - Arguments are validated on the host before anything is launched; a call that returns
+ *     an error has launched nothing.  mts_last_error() describes the last error of the
+ *     calling thread.
+ *   - Device-resident metadata (page ids, lengths) cannot be validated on the host.  The
+ *     kernels skip any access whose page id is outside [0, num_pages) or whose token lies
+ *     beyond the user's page list, so bad metadata gives wrong results, not a fault.
+ *
+ * Paged pool layout (fixed by this header; the paper's [L, N_pages, 2, S_page, H, D] of
+ * Sec. 4.1 is replaced by an arrangement whose 16-byte granules are MFMA operands):
+ *   layer l        at pool + l * layer_stride_bytes
+ *   page  p        at + p * page_bytes,            page_bytes = 2 * H * S * D * es
+ *   head  h        at + h * (2 * S * D * es)       (K block, then V block, S*D*es bytes each)
+ *   a page of S tokens is S/16 sub-blocks of 16 tokens; sub-block b at + b * 16 * D * es
+ *   inside a 16-token K sub-block, with G = 16 / es elements per granule,
+ *     element (token t, dim d) sits at element index
+ *       ((half * (D/G) + d/G) * 8 + slot) * G + d % G
+ *     where half = (t / 4) % 2 and slot = (t / 8) * 4 + t % 4;
+ *   inside a 16-token V sub-block the block is transposed:
+ *     element (token t, dim d) sits at element index  d * 16 + t.
+ *   mts_elem_offset() evaluates this map on the host.
+ *
+ * Contiguous ("host") layout of a run of n tokens of one user and one layer:
+ *   [2 (K plane, V plane)][n][H][D], i.e. what is kept in host chunks and what the onload
+ *   and offload buffers hold (Sec. 4.1 CPU tier, Sec. 4.2).
+ *
+ * Supported: dtype f32 or bf16; head_dim in {32, 64, 128}; page_size in {16, 32, 64};
+ * any num_heads >= 1.
+ */
+#ifndef MTSERVE_H
+#define MTSERVE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MTS_OK = 0,
+  MTS_ERR_INVALID_ARG = -1, /* null pointer, negative count, layer out of range, bad alignment */
+  MTS_ERR_UNSUPPORTED = -2, /* dtype / head_dim / page_size outside the supported set */
+  MTS_ERR_SHAPE = -3,       /* sizes inconsistent with each other */
+  MTS_ERR_WORKSPACE = -4,   /* workspace missing or too small */
+  MTS_ERR_HIP = -5          /* the HIP runtime refused a launch or a copy */
+};
+
+enum { MTS_F32 = 0, MTS_BF16 = 1 };
+
+/* The paged pool (Sec. 4.1 "Paged Store").  Plain data, read during the call only. */
+typedef struct mts_cache_desc {
+  void*   pool;               /* device, 256-byte aligned */
+  int64_t layer_stride_bytes; /* >= num_pages * page_bytes, multiple of 256 */
+  int32_t dtype;              /* MTS_F32 or MTS_BF16 */
+  int32_t num_layers;
+  int32_t num_pages;          /* pages per layer */
+  int32_t page_size;          /* tokens per page, S */
+  int32_t num_heads;          /* H (queries, keys and values share it) */
+  int32_t head_dim;           /* D */
+} mts_cache_desc;
+
+/* Per-batch metadata in the paper's vocabulary (Alg. 1 step 8.2: position / offsets /
+ * indices / indptr).  The int32 arrays are DEVICE arrays; the scalars are host copies the
+ * launch shapes are derived from and must bound the device contents. */
+typedef struct mts_batch_meta {
+  int32_t        batch;         /* B, users in the batch */
+  const int32_t* page_indptr;   /* device [B+1]: user u owns page_indices[page_indptr[u] .. page_indptr[u+1]) */
+  const int32_t* page_indices;  /* device [total_pages]: physical page ids in logical order */
+  const int32_t* prefix_lens;   /* device [B]: P_u, tokens valid in the cache before this step */
+  const int32_t* new_indptr;    /* device [B+1]: ragged offsets of the step's tokens in q/k_new/v_new/out */
+  int32_t        total_new;     /* = new_indptr[B] */
+  int32_t        max_new;       /* >= max_u n_u */
+  int32_t        max_total_len; /* >= max_u (P_u + n_u) */
+  int32_t        total_pages;   /* = page_indptr[B] */
+} mts_batch_meta;
+
+/* Bytes of one page of one layer: 2 * H * S * D * es.  Returns < 0 on a bad descriptor. */
+int64_t mts_page_bytes(const mts_cache_desc* cache);
+
+/* ceil(len / page_size): pages ONE user needs (rounding is per user, App. C.1). */
+int32_t mts_pages_for(int32_t len, int32_t page_size);
+
+/* Byte offset inside a page of element (kv: 0 = K, 1 = V; head; token slot in [0, S);
+ * dim in [0, D)) under the layout stated above.  Host-only; < 0 on bad arguments. */
+int64_t mts_elem_offset(const mts_cache_desc* cache, int32_t kv, int32_t head,
+                        int32_t slot, int32_t dim);
+
+/*
+ * Cache Scattering (Sec. 3.2 step 3; Sec. 4.2 scatter kernel).
+ * For segment s in [0, num_segs): user u = seg_user[s]; the run of n_s =
+ * seg_tok_indptr[s+1] - seg_tok_indptr[s] tokens that starts at element
+ * seg_tok_indptr[s] * 2*H*D of `staging` (contiguous layout [2][n_s][H][D]) becomes the
+ * user's tokens seg_pos[s] .. seg_pos[s]+n_s-1 in layer `layer`.  Exactly those slots are
+ * written, byte for byte; nothing else in the pool changes.
+ *   staging         device, 16-byte aligned; filled e.g. by hipMemcpyAsync from pinned host
+ *   seg_user        device int32 [num_segs], values in [0, meta->batch)
+ *   seg_pos         device int32 [num_segs], first destination token of the run
+ *   seg_tok_indptr  device int64 [num_segs+1], non-decreasing token offsets
+ *   max_seg_tokens  host, >= max_s n_s (launch shape)
+ * Uses meta->page_indptr / page_indices only.  num_segs == 0 is a no-op.
+ */
+int32_t mts_kv_unpack(const mts_cache_desc* cache, int32_t layer, const void* staging,
+                      int32_t num_segs, const int32_t* seg_user, const int32_t* seg_pos,
+                      const int64_t* seg_tok_indptr, int32_t max_seg_tokens,
+                      const mts_batch_meta* meta, void* stream);
+
+/*
+ * Cache Offload, gather half (Sec. 3.2 step 6; Sec. 4.2 gather kernel).  Exact inverse of
+ * mts_kv_unpack: tokens seg_pos[s] .. +n_s-1 of user seg_user[s] are copied from the pages
+ * into `staging_out` (device, 16-byte aligned) in the contiguous layout, ready for a
+ * device-to-host copy.  The pool is not modified.
+ */
+int32_t mts_kv_pack(const mts_cache_desc* cache, int32_t layer, void* staging_out,
+                    int32_t num_segs, const int32_t* seg_user, const int32_t* seg_pos,
+                    const int64_t* seg_tok_indptr, int32_t max_seg_tokens,
+                    const mts_batch_meta* meta, void* stream);
+
+/*
+ * Cache Update (Sec. 3.2 step 5; Alg. 1 step 8.2).  k_new / v_new are device [total_new][H][D]
+ * (16-byte aligned), ragged over users by meta->new_indptr; user u's i-th row is written at
+ * token position prefix_lens[u] + i of layer `layer`.  The pages must already be in the
+ * user's page list.  total_new == 0 is a no-op.
+ */
+int32_t mts_kv_append(const mts_cache_desc* cache, int32_t layer, const void* k_new,
+                      const void* v_new, const mts_batch_meta* meta, void* stream);
+
+/* Workspace mts_attn_incremental needs for this cache and batch shape (host-only, >= 0;
+ * < 0 on bad arguments).  The workspace is device memory, 256-byte aligned, and may be
+ * reused by later calls on the same stream. */
+int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_meta* meta);
+
+/*
+ * Incremental-prefill attention (Sec. 2, Eq. 6-7; Alg. 1 step 8.4).  For user u, head h and
+ * new token i at absolute position p = prefix_lens[u] + i:
+ *     out[i, h, :] = sum_j softmax_j(sm_scale * q[i, h, :] . K[j, h, :]) * V[j, h, :],  j in [0, p]
+ * with K/V rows 0..p read from the user's pages of layer `layer`: the whole cached prefix is
+ * visible and the new tokens are causal among themselves.  The step's own K/V must already
+ * have been appended (mts_kv_append enqueued earlier on the same stream), as Alg. 1 orders it.
+ * prefix_lens[u] == 0 gives plain causal prefill (the cache-miss / recompute shape).
+ *   q, out     device [total_new][H][D], cache dtype, 16-byte aligned; out is overwritten
+ *   sm_scale   logit scale; 0 selects 1/sqrt(D)
+ * Logits, softmax statistics and accumulators are fp32.  For bf16 the softmax weights are
+ * rounded to bf16 before the weighted sum of V (matrix-core operand) and the result is
+ * rounded to bf16 (nearest even).
+ */
+int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const void* q,
+                             void* out, const mts_batch_meta* meta, float sm_scale,
+                             void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Host<->device staging copies on `stream` (hipMemcpyAsync); `host` should be pinned for the
+ * copy to be asynchronous (Sec. 4.2, DMA between pinned buffers and the onload / offload buffers). */
+int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream);
+int32_t mts_stage_d2h_async(void* host_dst, const void* device_src, int64_t bytes, void* stream);
+
+/* Text of the calling thread's last error ("" if none).  Never NULL. */
+const char* mts_last_error(void);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int32_t mts_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTSERVE_H */

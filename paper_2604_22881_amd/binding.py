@@ -1,0 +1,164 @@
+"""ctypes binding of libmtserve_hip.so: the same entry points as include/mtserve.h.
+
+Argument marshalling only - every step of the path runs in the HIP kernels.  PyTorch is
+used for device memory and streams.  There is no fallback: if the shared library has not
+been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libmtserve_hip.so")
+
+MTS_OK, MTS_ERR_INVALID_ARG, MTS_ERR_UNSUPPORTED, MTS_ERR_SHAPE, MTS_ERR_WORKSPACE, MTS_ERR_HIP = 0, -1, -2, -3, -4, -5
+MTS_F32, MTS_BF16 = 0, 1
+
+EXPORTS = (
+    "mts_page_bytes", "mts_pages_for", "mts_elem_offset", "mts_kv_unpack", "mts_kv_pack",
+    "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental",
+    "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
+)
+
+
+class MtsError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"mtserve error {code}: {text}")
+        self.code = code
+
+
+class CacheDesc(C.Structure):
+    _fields_ = [("pool", C.c_void_p), ("layer_stride_bytes", C.c_int64), ("dtype", C.c_int32),
+                ("num_layers", C.c_int32), ("num_pages", C.c_int32), ("page_size", C.c_int32),
+                ("num_heads", C.c_int32), ("head_dim", C.c_int32)]
+
+
+class BatchMeta(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("page_indptr", C.c_void_p), ("page_indices", C.c_void_p),
+                ("prefix_lens", C.c_void_p), ("new_indptr", C.c_void_p), ("total_new", C.c_int32),
+                ("max_new", C.c_int32), ("max_total_len", C.c_int32), ("total_pages", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (loaded on first use)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2604_22881_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    P, I32, I64, F32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    DESC, META = C.POINTER(CacheDesc), C.POINTER(BatchMeta)
+    sig = {
+        "mts_page_bytes": (I64, [DESC]),
+        "mts_pages_for": (I32, [I32, I32]),
+        "mts_elem_offset": (I64, [DESC, I32, I32, I32, I32]),
+        "mts_kv_unpack": (I32, [DESC, I32, P, I32, P, P, P, I32, META, P]),
+        "mts_kv_pack": (I32, [DESC, I32, P, I32, P, P, P, I32, META, P]),
+        "mts_kv_append": (I32, [DESC, I32, P, P, META, P]),
+        "mts_attn_workspace_bytes": (I64, [DESC, META]),
+        "mts_attn_incremental": (I32, [DESC, I32, P, P, META, F32, P, I64, P]),
+        "mts_stage_h2d_async": (I32, [P, P, I64, P]),
+        "mts_stage_d2h_async": (I32, [P, P, I64, P]),
+        "mts_last_error": (C.c_char_p, []),
+        "mts_version": (I32, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+def _check(code):
+    if code < 0:
+        raise MtsError(int(code), lib().mts_last_error().decode())
+    return code
+
+
+def _ptr(x):
+    """Address of a torch tensor / numpy array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+# ---- host-only helpers ------------------------------------------------------------------
+def mts_version():
+    return lib().mts_version()
+
+
+def mts_last_error():
+    return lib().mts_last_error().decode()
+
+
+def mts_page_bytes(desc: CacheDesc):
+    return _check(lib().mts_page_bytes(C.byref(desc)))
+
+
+def mts_pages_for(length, page_size):
+    return _check(lib().mts_pages_for(length, page_size))
+
+
+def mts_elem_offset(desc: CacheDesc, kv, head, slot, dim):
+    return _check(lib().mts_elem_offset(C.byref(desc), kv, head, slot, dim))
+
+
+def mts_attn_workspace_bytes(desc: CacheDesc, meta: BatchMeta):
+    return _check(lib().mts_attn_workspace_bytes(C.byref(desc), C.byref(meta)))
+
+
+# ---- device entry points ----------------------------------------------------------------
+def mts_kv_unpack(desc, layer, staging, num_segs, seg_user, seg_pos, seg_tok_indptr, max_seg_tokens,
+                  meta, stream=None):
+    return _check(lib().mts_kv_unpack(C.byref(desc), layer, _ptr(staging), num_segs, _ptr(seg_user),
+                                      _ptr(seg_pos), _ptr(seg_tok_indptr), max_seg_tokens,
+                                      C.byref(meta), _stream(stream)))
+
+
+def mts_kv_pack(desc, layer, staging_out, num_segs, seg_user, seg_pos, seg_tok_indptr, max_seg_tokens,
+                meta, stream=None):
+    return _check(lib().mts_kv_pack(C.byref(desc), layer, _ptr(staging_out), num_segs, _ptr(seg_user),
+                                    _ptr(seg_pos), _ptr(seg_tok_indptr), max_seg_tokens,
+                                    C.byref(meta), _stream(stream)))
+
+
+def mts_kv_append(desc, layer, k_new, v_new, meta, stream=None):
+    return _check(lib().mts_kv_append(C.byref(desc), layer, _ptr(k_new), _ptr(v_new), C.byref(meta),
+                                      _stream(stream)))
+
+
+def mts_attn_incremental(desc, layer, q, out, meta, sm_scale=0.0, workspace=None, workspace_bytes=0,
+                         stream=None):
+    return _check(lib().mts_attn_incremental(C.byref(desc), layer, _ptr(q), _ptr(out), C.byref(meta),
+                                             float(sm_scale), _ptr(workspace), int(workspace_bytes),
+                                             _stream(stream)))
+
+
+def mts_stage_h2d_async(device_dst, host_src, nbytes, stream=None):
+    return _check(lib().mts_stage_h2d_async(_ptr(device_dst), _ptr(host_src), int(nbytes), _stream(stream)))
+
+
+def mts_stage_d2h_async(host_dst, device_src, nbytes, stream=None):
+    return _check(lib().mts_stage_d2h_async(_ptr(host_dst), _ptr(device_src), int(nbytes), _stream(stream)))

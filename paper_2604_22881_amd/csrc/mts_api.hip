@@ -1,0 +1,289 @@
+// C ABI of the library: argument validation on the host, then the launchers.
+// Every entry point returns before launching anything if an argument is bad.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/mtserve.h"
+#include "mts_internal.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int elem_bytes(int32_t dtype) { return dtype == MTS_F32 ? 4 : (dtype == MTS_BF16 ? 2 : 0); }
+
+// Validates the descriptor (and the layer, unless layer < -1 is passed as "not needed").
+int32_t check_cache(const mts_cache_desc* c, int32_t layer, bool need_pool, mts::PoolGeom* g) {
+  if (!c) return fail(MTS_ERR_INVALID_ARG, "cache descriptor is NULL");
+  const int es = elem_bytes(c->dtype);
+  if (!es) return fail(MTS_ERR_UNSUPPORTED, "dtype %d is neither MTS_F32 nor MTS_BF16", c->dtype);
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128)
+    return fail(MTS_ERR_UNSUPPORTED, "head_dim %d not in {32, 64, 128}", c->head_dim);
+  if (c->page_size != 16 && c->page_size != 32 && c->page_size != 64)
+    return fail(MTS_ERR_UNSUPPORTED, "page_size %d not in {16, 32, 64}", c->page_size);
+  if (c->num_heads < 1 || c->num_heads > 65535)
+    return fail(MTS_ERR_INVALID_ARG, "num_heads %d out of range [1, 65535]", c->num_heads);
+  if (c->num_layers < 1 || c->num_pages < 1)
+    return fail(MTS_ERR_INVALID_ARG, "num_layers %d and num_pages %d must be >= 1", c->num_layers, c->num_pages);
+  const int64_t page_bytes = 2ll * c->num_heads * c->page_size * c->head_dim * es;
+  if (need_pool) {
+    if (!c->pool) return fail(MTS_ERR_INVALID_ARG, "pool is NULL");
+    if (!aligned(c->pool, 256)) return fail(MTS_ERR_INVALID_ARG, "pool is not 256-byte aligned");
+    if (c->layer_stride_bytes < page_bytes * c->num_pages)
+      return fail(MTS_ERR_SHAPE, "layer_stride_bytes %lld < num_pages * page_bytes %lld",
+                  (long long)c->layer_stride_bytes, (long long)(page_bytes * c->num_pages));
+    if (c->layer_stride_bytes % 256)
+      return fail(MTS_ERR_INVALID_ARG, "layer_stride_bytes is not a multiple of 256");
+    if (layer < 0 || layer >= c->num_layers)
+      return fail(MTS_ERR_INVALID_ARG, "layer %d out of range [0, %d)", layer, c->num_layers);
+  }
+  if (g) {
+    g->layer_base = need_pool ? static_cast<char*>(c->pool) + (int64_t)layer * c->layer_stride_bytes : nullptr;
+    g->page_bytes = page_bytes;
+    g->num_pages = c->num_pages;
+    g->S = c->page_size;
+    g->H = c->num_heads;
+    g->D = c->head_dim;
+    g->es = es;
+    g->sub_shift = c->page_size == 16 ? 0 : (c->page_size == 32 ? 1 : 2);
+  }
+  return MTS_OK;
+}
+
+int32_t check_meta(const mts_batch_meta* m, bool need_new, bool need_ptrs, mts::BatchDev* b) {
+  if (!m) return fail(MTS_ERR_INVALID_ARG, "batch metadata is NULL");
+  if (m->batch < 0 || m->batch > 65535) return fail(MTS_ERR_INVALID_ARG, "batch %d out of range [0, 65535]", m->batch);
+  if (m->total_pages < 0 || m->total_new < 0 || m->max_new < 0 || m->max_total_len < 0)
+    return fail(MTS_ERR_INVALID_ARG, "negative count in batch metadata");
+  if (need_ptrs && m->batch > 0) {
+    if (!m->page_indptr || !m->page_indices)
+      return fail(MTS_ERR_INVALID_ARG, "page_indptr / page_indices is NULL");
+    if (need_new && (!m->prefix_lens || !m->new_indptr))
+      return fail(MTS_ERR_INVALID_ARG, "prefix_lens / new_indptr is NULL");
+  }
+  if (need_new) {
+    if ((int64_t)m->total_new > (int64_t)m->batch * m->max_new)
+      return fail(MTS_ERR_SHAPE, "total_new %d exceeds batch %d * max_new %d", m->total_new, m->batch, m->max_new);
+    if (m->max_new > m->max_total_len)
+      return fail(MTS_ERR_SHAPE, "max_new %d exceeds max_total_len %d", m->max_new, m->max_total_len);
+  }
+  if (b) {
+    b->batch = m->batch;
+    b->page_indptr = m->page_indptr;
+    b->page_indices = m->page_indices;
+    b->prefix_lens = m->prefix_lens;
+    b->new_indptr = m->new_indptr;
+    b->total_new = m->total_new;
+    b->max_new = m->max_new;
+    b->max_total_len = m->max_total_len;
+    b->total_pages = m->total_pages;
+  }
+  return MTS_OK;
+}
+
+int32_t check_segs(int32_t num_segs, const int32_t* seg_user, const int32_t* seg_pos,
+                   const int64_t* seg_tok_indptr, int32_t max_seg_tokens, mts::SegDev* s) {
+  if (num_segs < 0 || num_segs > 65535)
+    return fail(MTS_ERR_INVALID_ARG, "num_segs %d out of range [0, 65535]", num_segs);
+  if (max_seg_tokens < 0) return fail(MTS_ERR_INVALID_ARG, "max_seg_tokens is negative");
+  if (num_segs > 0 && (!seg_user || !seg_pos || !seg_tok_indptr))
+    return fail(MTS_ERR_INVALID_ARG, "segment array is NULL");
+  s->num_segs = num_segs;
+  s->seg_user = seg_user;
+  s->seg_pos = seg_pos;
+  s->seg_tok_indptr = seg_tok_indptr;
+  s->max_seg_tokens = max_seg_tokens;
+  return MTS_OK;
+}
+
+int32_t hip_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return MTS_OK;
+  return fail(MTS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int roundup(int64_t v, int m) { return (int)((v + m - 1) / m * m); }
+
+}  // namespace
+
+namespace mts {
+
+AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
+  AttnPlan p{};
+  p.use_mfma = (g.es == 2);
+  if (!p.use_mfma || b.total_new <= 0 || b.batch <= 0) {
+    p.q_tile = 16; p.q_tiles_max = 1; p.chunk = 128; p.chunks_max = 1; p.ws_bytes = 0;
+    return p;
+  }
+  const int max_new = b.max_new > 0 ? b.max_new : 1;
+  p.q_tile = roundup(max_new, 16) < 64 ? roundup(max_new, 16) : 64;
+  p.q_tiles_max = (max_new + p.q_tile - 1) / p.q_tile;
+  const int full = roundup(b.max_total_len > 0 ? b.max_total_len : 1, 128);
+  // (user, query tile, head) triples already in flight; split the kv axis only when they
+  // cannot fill the chip by themselves.
+  const int64_t rows = (int64_t)b.batch * p.q_tiles_max * g.H;
+  int chunk = full;
+  if (rows < 2048) {
+    // aim for a few thousand workgroups of equal kv length; never below 256 tokens, where
+    // the partial accumulators would rival the K/V traffic itself
+    int64_t kv_tokens = (int64_t)b.batch * b.max_total_len;
+    if (b.total_pages > 0 && (int64_t)b.total_pages * g.S < kv_tokens) kv_tokens = (int64_t)b.total_pages * g.S;
+    chunk = roundup(kv_tokens * g.H * p.q_tiles_max / 4096 + 1, 128);
+    if (chunk < 256) chunk = 256;
+    if (chunk > full) chunk = full;
+  }
+  if (const char* env = getenv("MTS_ATTN_CHUNK")) {
+    const int v = atoi(env);
+    if (v >= 128) chunk = roundup(v, 128) < full ? roundup(v, 128) : full;
+  }
+  p.chunk = chunk;
+  p.chunks_max = (full + chunk - 1) / chunk;
+  if (p.chunks_max < 1) p.chunks_max = 1;
+  p.ws_bytes = p.chunks_max > 1
+                   ? (int64_t)b.total_new * g.H * p.chunks_max * (g.D + 2) * (int64_t)sizeof(float)
+                   : 0;
+  return p;
+}
+
+}  // namespace mts
+
+extern "C" {
+
+const char* mts_last_error(void) { return g_err; }
+
+int32_t mts_version(void) { return 100; }
+
+int64_t mts_page_bytes(const mts_cache_desc* cache) {
+  mts::PoolGeom g{};
+  const int32_t st = check_cache(cache, 0, false, &g);
+  return st != MTS_OK ? st : g.page_bytes;
+}
+
+int32_t mts_pages_for(int32_t len, int32_t page_size) {
+  if (len < 0 || page_size <= 0) return fail(MTS_ERR_INVALID_ARG, "len >= 0 and page_size > 0 required");
+  return (int32_t)(((int64_t)len + page_size - 1) / page_size);
+}
+
+int64_t mts_elem_offset(const mts_cache_desc* cache, int32_t kv, int32_t head, int32_t slot, int32_t dim) {
+  mts::PoolGeom g{};
+  const int32_t st = check_cache(cache, 0, false, &g);
+  if (st != MTS_OK) return st;
+  if (kv < 0 || kv > 1 || head < 0 || head >= g.H || slot < 0 || slot >= g.S || dim < 0 || dim >= g.D)
+    return fail(MTS_ERR_INVALID_ARG, "element (kv %d, head %d, slot %d, dim %d) out of range", kv, head, slot, dim);
+  return mts::elem_offset(kv, head, slot, dim, g.S, g.D, g.es);
+}
+
+int32_t mts_kv_unpack(const mts_cache_desc* cache, int32_t layer, const void* staging, int32_t num_segs,
+                      const int32_t* seg_user, const int32_t* seg_pos, const int64_t* seg_tok_indptr,
+                      int32_t max_seg_tokens, const mts_batch_meta* meta, void* stream) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  mts::SegDev s{};
+  int32_t st;
+  if ((st = check_cache(cache, layer, true, &g)) != MTS_OK) return st;
+  if ((st = check_meta(meta, false, true, &b)) != MTS_OK) return st;
+  if ((st = check_segs(num_segs, seg_user, seg_pos, seg_tok_indptr, max_seg_tokens, &s)) != MTS_OK) return st;
+  if (num_segs == 0 || max_seg_tokens == 0) return MTS_OK;
+  if (!staging) return fail(MTS_ERR_INVALID_ARG, "staging is NULL");
+  if (!aligned(staging, 16)) return fail(MTS_ERR_INVALID_ARG, "staging is not 16-byte aligned");
+  if (b.batch == 0) return fail(MTS_ERR_SHAPE, "segments given for an empty batch");
+  return hip_status(mts::launch_unpack(g, staging, s, b, static_cast<hipStream_t>(stream)), "mts_kv_unpack launch");
+}
+
+int32_t mts_kv_pack(const mts_cache_desc* cache, int32_t layer, void* staging_out, int32_t num_segs,
+                    const int32_t* seg_user, const int32_t* seg_pos, const int64_t* seg_tok_indptr,
+                    int32_t max_seg_tokens, const mts_batch_meta* meta, void* stream) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  mts::SegDev s{};
+  int32_t st;
+  if ((st = check_cache(cache, layer, true, &g)) != MTS_OK) return st;
+  if ((st = check_meta(meta, false, true, &b)) != MTS_OK) return st;
+  if ((st = check_segs(num_segs, seg_user, seg_pos, seg_tok_indptr, max_seg_tokens, &s)) != MTS_OK) return st;
+  if (num_segs == 0 || max_seg_tokens == 0) return MTS_OK;
+  if (!staging_out) return fail(MTS_ERR_INVALID_ARG, "staging_out is NULL");
+  if (!aligned(staging_out, 16)) return fail(MTS_ERR_INVALID_ARG, "staging_out is not 16-byte aligned");
+  if (b.batch == 0) return fail(MTS_ERR_SHAPE, "segments given for an empty batch");
+  return hip_status(mts::launch_pack(g, staging_out, s, b, static_cast<hipStream_t>(stream)), "mts_kv_pack launch");
+}
+
+int32_t mts_kv_append(const mts_cache_desc* cache, int32_t layer, const void* k_new, const void* v_new,
+                      const mts_batch_meta* meta, void* stream) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  int32_t st;
+  if ((st = check_cache(cache, layer, true, &g)) != MTS_OK) return st;
+  if ((st = check_meta(meta, true, true, &b)) != MTS_OK) return st;
+  if (b.batch == 0 || b.total_new == 0) return MTS_OK;
+  if (!k_new || !v_new) return fail(MTS_ERR_INVALID_ARG, "k_new / v_new is NULL");
+  if (!aligned(k_new, 16) || !aligned(v_new, 16))
+    return fail(MTS_ERR_INVALID_ARG, "k_new / v_new is not 16-byte aligned");
+  return hip_status(mts::launch_append(g, k_new, v_new, b, static_cast<hipStream_t>(stream)), "mts_kv_append launch");
+}
+
+int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_meta* meta) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  int32_t st;
+  if ((st = check_cache(cache, 0, false, &g)) != MTS_OK) return st;
+  if ((st = check_meta(meta, true, false, &b)) != MTS_OK) return st;
+  return mts::plan_attention(g, b).ws_bytes;
+}
+
+int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
+                             const mts_batch_meta* meta, float sm_scale, void* workspace,
+                             int64_t workspace_bytes, void* stream) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  int32_t st;
+  if ((st = check_cache(cache, layer, true, &g)) != MTS_OK) return st;
+  if ((st = check_meta(meta, true, true, &b)) != MTS_OK) return st;
+  if (!(sm_scale >= 0.f) || sm_scale > 1e30f)
+    return fail(MTS_ERR_INVALID_ARG, "sm_scale must be finite and >= 0 (0 selects 1/sqrt(D))");
+  if (b.batch == 0 || b.total_new == 0) return MTS_OK;
+  if (!q || !out) return fail(MTS_ERR_INVALID_ARG, "q / out is NULL");
+  if (!aligned(q, 16) || !aligned(out, 16)) return fail(MTS_ERR_INVALID_ARG, "q / out is not 16-byte aligned");
+  const mts::AttnPlan plan = mts::plan_attention(g, b);
+  if (plan.ws_bytes > 0) {
+    if (!workspace) return fail(MTS_ERR_WORKSPACE, "workspace is NULL but %lld bytes are needed", (long long)plan.ws_bytes);
+    if (workspace_bytes < plan.ws_bytes)
+      return fail(MTS_ERR_WORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes,
+                  (long long)plan.ws_bytes);
+    if (!aligned(workspace, 256)) return fail(MTS_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  }
+  const float scale = sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)g.D);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (plan.use_mfma && !getenv("MTS_ATTN_PLAIN"))
+    return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, plan.ws_bytes > 0 ? workspace : nullptr, s),
+                      "mts_attn_incremental launch");
+  return hip_status(mts::launch_attn_generic(g, q, out, b, scale, s), "mts_attn_incremental launch");
+}
+
+int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream) {
+  if (bytes < 0) return fail(MTS_ERR_INVALID_ARG, "negative byte count");
+  if (bytes == 0) return MTS_OK;
+  if (!device_dst || !host_src) return fail(MTS_ERR_INVALID_ARG, "NULL pointer");
+  return hip_status(hipMemcpyAsync(device_dst, host_src, (size_t)bytes, hipMemcpyHostToDevice,
+                                   static_cast<hipStream_t>(stream)), "host-to-device staging copy");
+}
+
+int32_t mts_stage_d2h_async(void* host_dst, const void* device_src, int64_t bytes, void* stream) {
+  if (bytes < 0) return fail(MTS_ERR_INVALID_ARG, "negative byte count");
+  if (bytes == 0) return MTS_OK;
+  if (!host_dst || !device_src) return fail(MTS_ERR_INVALID_ARG, "NULL pointer");
+  return hip_status(hipMemcpyAsync(host_dst, device_src, (size_t)bytes, hipMemcpyDeviceToHost,
+                                   static_cast<hipStream_t>(stream)), "device-to-host staging copy");
+}
+
+}  // extern "C"

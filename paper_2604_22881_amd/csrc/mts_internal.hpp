@@ -1,0 +1,54 @@
+// Launchers behind the C ABI.  Each takes validated arguments, enqueues its kernels on
+// `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mts_layout.hpp"
+
+namespace mts {
+
+struct BatchDev {            // device metadata arrays, as in mts_batch_meta
+  int32_t        batch;
+  const int32_t* page_indptr;
+  const int32_t* page_indices;
+  const int32_t* prefix_lens;
+  const int32_t* new_indptr;
+  int32_t        total_new;
+  int32_t        max_new;
+  int32_t        max_total_len;
+  int32_t        total_pages;
+};
+
+struct SegDev {              // segment lists of unpack / pack
+  int32_t        num_segs;
+  const int32_t* seg_user;
+  const int32_t* seg_pos;
+  const int64_t* seg_tok_indptr;
+  int32_t        max_seg_tokens;
+};
+
+hipError_t launch_unpack(const PoolGeom& g, const void* staging, const SegDev& segs,
+                         const BatchDev& b, hipStream_t stream);
+hipError_t launch_pack(const PoolGeom& g, void* staging_out, const SegDev& segs,
+                       const BatchDev& b, hipStream_t stream);
+hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new,
+                         const BatchDev& b, hipStream_t stream);
+
+// Shape plan of one attention call: computed on the host from the scalar bounds only.
+struct AttnPlan {
+  bool    use_mfma;      // bf16 matrix-core kernel, else the plain fp32-accumulate kernel
+  int32_t q_tile;        // queries per workgroup (multiple of 16, <= 64)
+  int32_t q_tiles_max;   // ceil(max_new / q_tile)
+  int32_t chunk;         // kv tokens per workgroup (multiple of 128)
+  int32_t chunks_max;    // ceil(max_total_len / chunk)
+  int64_t ws_bytes;      // partial accumulators + softmax statistics
+};
+AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b);
+
+hipError_t launch_attn_generic(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
+                               float sm_scale, hipStream_t stream);
+hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
+                            const BatchDev& b, float sm_scale, void* workspace, hipStream_t stream);
+
+}  // namespace mts

@@ -1,0 +1,115 @@
+"""Runs one step of a workload through the C ABI on the GPU (history staged and unpacked in
+host-chunk runs, new K/V appended, attention, pack) and hands back host arrays."""
+import numpy as np
+import torch
+
+import mts_workloads as W
+import paper_2604_22881_amd as mts
+from paper_2604_22881_amd.runtime import DeviceBatch, PagedKVCache, SegmentList
+
+DEV = "cuda:0"
+
+
+def torch_dtype(w):
+    return torch.float32 if w.dtype == "f32" else torch.uint16
+
+
+def to_dev(raw):
+    """numpy float32 / uint16(bf16 bits) -> device tensor of the same bits."""
+    raw = np.ascontiguousarray(raw)
+    if raw.dtype == np.uint16:
+        return torch.from_numpy(raw.view(np.int16)).to(DEV)
+    return torch.from_numpy(raw).to(DEV)
+
+
+def to_host(t, np_dtype):
+    a = t.cpu().numpy()
+    return a.view(np_dtype) if a.dtype != np_dtype else a
+
+
+class GpuStep:
+    def __init__(self, w, fill_byte=0xFF):
+        self.w = w
+        self.cache = PagedKVCache(w.layers, w.num_pages, w.page_size, w.heads, w.head_dim, w.dtype,
+                                  DEV, fill_byte=fill_byte)
+        self.batch = DeviceBatch.from_workload(w, DEV)
+        self.ws_bytes = mts.mts_attn_workspace_bytes(self.cache.desc, self.batch.meta)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=DEV)
+
+    def unpack_histories(self, data, layer, users=None, chunk=None):
+        w = self.w
+        users = range(w.batch) if users is None else users
+        users = [u for u in users if w.prefix_lens[u] > 0]
+        if not users:
+            return
+        segs = SegmentList.for_histories(users, [w.prefix_lens[u] for u in users],
+                                         chunk or w.chunk_tokens, DEV)
+        # staging buffer: each run is [2][n][H][D], runs concatenated in segment order
+        host = []
+        su = segs.seg_user.cpu().numpy(); sp = segs.seg_pos.cpu().numpy()
+        cnt = np.diff(segs.host_indptr)
+        for s in range(segs.num_segs):
+            host.append(np.ascontiguousarray(data["hist"][layer][su[s]][:, sp[s]:sp[s] + cnt[s]]).reshape(-1))
+        staging = to_dev(np.concatenate(host))
+        mts.mts_kv_unpack(self.cache.desc, layer, staging, *segs.args(), self.batch.meta)
+        torch.cuda.synchronize()
+
+    def append(self, data, layer):
+        k, v = to_dev(data["k_new"][layer]), to_dev(data["v_new"][layer])
+        mts.mts_kv_append(self.cache.desc, layer, k, v, self.batch.meta)
+        torch.cuda.synchronize()
+
+    def attention(self, data, layer, sm_scale=0.0):
+        w = self.w
+        q = to_dev(data["q"][layer])
+        out = torch.full((max(w.total_new, 1), w.heads, w.head_dim), -1, dtype=q.dtype, device=DEV)
+        mts.mts_attn_incremental(self.cache.desc, layer, q, out, self.batch.meta, sm_scale,
+                                 self.ws, self.ws_bytes)
+        torch.cuda.synchronize()
+        return to_host(out[:w.total_new], w.np_dtype)
+
+    def pack(self, layer, users, positions, counts):
+        w = self.w
+        segs = SegmentList(users, positions, counts, DEV)
+        n_elem = segs.total_tokens * 2 * w.heads * w.head_dim
+        out = torch.zeros(max(n_elem, 8), dtype=torch.float32 if w.dtype == "f32" else torch.int16, device=DEV)
+        mts.mts_kv_pack(self.cache.desc, layer, out, *segs.args(), self.batch.meta)
+        torch.cuda.synchronize()
+        flat = to_host(out[:n_elem], w.np_dtype)
+        res, off = [], 0
+        for n in counts:
+            sz = 2 * int(n) * w.heads * w.head_dim
+            res.append(flat[off:off + sz].reshape(2, int(n), w.heads, w.head_dim))
+            off += sz
+        return res
+
+    def pool_image(self, layer):
+        return self.cache.layer_bytes(layer).cpu().numpy()
+
+
+def expected_pool_image(w, store, layer, fill_byte):
+    """Byte image of one layer of the GPU pool implied by the oracle store's owned slots,
+    under the layout the C header documents (written out here independently of the library):
+    page -> head -> {K block, V block}; 16-token sub-blocks; K granule order
+    [half][D/G][8 slots][G], V transposed [D][16]."""
+    S, H, D, es = w.page_size, w.heads, w.head_dim, w.elem_bytes
+    G = 16 // es
+    t = np.arange(S)
+    sub, t16 = t // 16, t % 16
+    half, slot8 = (t16 // 4) % 2, (t16 // 8) * 4 + t16 % 4
+    d = np.arange(D)
+    k_idx = (sub * 16 * D)[:, None] + ((half[:, None] * (D // G) + d[None, :] // G) * 8 + slot8[:, None]) * G + d[None, :] % G
+    v_idx = (sub * 16 * D)[:, None] + d[None, :] * 16 + t16[:, None]
+    head_base = np.arange(H) * 2 * S * D
+    # element offsets [kv][slot][head][dim] inside a page
+    off = np.stack([head_base[None, :, None] + k_idx[:, None, :],
+                    head_base[None, :, None] + S * D + v_idx[:, None, :]])
+    page_elems = 2 * H * S * D
+    img = np.full((w.num_pages, page_elems * es), fill_byte, dtype=np.uint8).view(w.np_dtype)
+    for u in range(w.batch):
+        pages = w.user_pages(u)
+        for tok in range(int(w.total_lens[u])):
+            p, sl = pages[tok // S], tok % S
+            for kv in (0, 1):
+                img[p, off[kv, sl]] = store.data[layer, p, kv, sl]
+    return img.view(np.uint8)
