@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path over one batch of the synthetic workload: per layer
+mts_kv_append then mts_attn_incremental on the compute stream, while a side stream restores
+the batch's cache-miss users from an HBM-resident staging buffer (mts_kv_unpack, one event per
+layer that the layer's attention waits for, as in Alg. 1 step 8.3) and packs the users chosen
+for offload (mts_kv_pack).  All inputs are resident in HBM before the timed region.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="batched_incremental")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
+    return ap.parse_args()
+
+
+def algorithmic_bytes_per_layer(w):
+    """Bytes one attention launch must move: every owned K and V row once, Q once, O once."""
+    row = w.heads * w.head_dim * w.elem_bytes
+    kv = int(w.total_lens.sum()) * 2 * row
+    qo = w.total_new * 2 * row
+    return kv, qo
+
+
+def attention_flops_per_layer(w):
+    """QK^T and PV multiply-adds over the visible (query, key) pairs only."""
+    pairs = sum(int(n) * int(P) + int(n) * (int(n) + 1) // 2 for P, n in zip(w.prefix_lens, w.new_lens))
+    return 4 * w.head_dim * w.heads * pairs
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample: whole users of the same workload, one
+    layer, all heads (unpack in host-chunk runs + append + attention + pack of one user)."""
+    import numpy as np
+    import oracle
+    import mts_workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    rng = np.random.default_rng([w.seed, 99])
+    done_tokens, t_used, users = 0, 0.0, 0
+    for u in range(w.batch):
+        P, n = int(w.prefix_lens[u]), int(w.new_lens[u])
+        sub = W.custom_workload("sample", w.seed + u, w.dtype, 1, w.heads, w.head_dim, w.page_size, [P], [n])
+        hist = W.normal_elements(rng, (2, P, w.heads, w.head_dim), w.dtype)
+        k = W.normal_elements(rng, (n, w.heads, w.head_dim), w.dtype)
+        v = W.normal_elements(rng, (n, w.heads, w.head_dim), w.dtype)
+        q = W.normal_elements(rng, (n, w.heads, w.head_dim), w.dtype)
+        t0 = time.perf_counter()
+        store = oracle.PagedStore(1, sub.num_pages, sub.page_size, sub.heads, sub.head_dim, sub.np_dtype)
+        for start, cnt in W.host_chunks(P, w.chunk_tokens):
+            oracle.unpack(store, 0, hist[:, start:start + cnt], sub.user_pages(0), start)
+        oracle.append(store, 0, k, v, sub.page_indptr, sub.page_indices, sub.prefix_lens, sub.new_indptr)
+        oracle.attn_incremental(store, 0, q, sub.page_indptr, sub.page_indices, sub.prefix_lens, sub.new_indptr)
+        t_used += time.perf_counter() - t0
+        done_tokens += n
+        users += 1
+        if t_used > budget_s:
+            break
+    # one layer was timed; a step runs all layers over the same tokens
+    value = done_tokens / (t_used * w.layers)
+    return {"value": value, "unit": "new_tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{users} of {w.batch} users (whole histories), 1 of {w.layers} layers timed and "
+                      f"scaled to {w.layers}; unpack+append+attention, fp64, {t_used:.1f} s of CPU work"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
+              "(the path shards by user with no exchange step; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import mts_workloads as W
+    import paper_2604_22881_amd as mts
+    from paper_2604_22881_amd.runtime import DeviceBatch, PagedKVCache, SegmentList
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.make_workload(args.workload)
+    assert w.dtype == "bf16", "the benchmark workloads are bf16"
+    L, H, D = w.layers, w.heads, w.head_dim
+    torch.manual_seed(w.seed)
+
+    # ---- inputs, resident in HBM before timing ------------------------------------------
+    cache = PagedKVCache(L, w.num_pages, w.page_size, H, D, w.dtype, dev)
+    cache.pool.view(torch.bfloat16).normal_()            # every slot ~ N(0,1): K/V of all users
+    batch = DeviceBatch.from_workload(w, dev)
+    N = w.total_new
+    q = [torch.randn(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
+    k_new = [torch.randn(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
+    v_new = [torch.randn(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
+    out = [torch.empty(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
+    ws_bytes = mts.mts_attn_workspace_bytes(cache.desc, batch.meta)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    miss = [int(u) for u in w.miss_users if w.prefix_lens[u] > 0]
+    miss_segs = SegmentList.for_histories(miss, [w.prefix_lens[u] for u in miss], w.chunk_tokens, dev)
+    staging = [torch.randn(max(miss_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
+               for _ in range(L)]                        # onload buffer contents, one per layer
+    evict = [int(u) for u in w.evict_users]
+    evict_segs = SegmentList.for_histories(evict, [w.total_lens[u] for u in evict], w.chunk_tokens, dev)
+    offload = torch.empty(max(evict_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
+
+    compute = torch.cuda.Stream(device=dev)
+    side = torch.cuda.Stream(device=dev)
+    ev_unpacked = [torch.cuda.Event() for _ in range(L)]
+    ev_appended = [torch.cuda.Event() for _ in range(L)]
+    cs, ss = compute.cuda_stream, side.cuda_stream
+
+    def step(attn_events=None):
+        for l in range(L):
+            if miss_segs.num_segs:
+                mts.mts_kv_unpack(cache.desc, l, staging[l], *miss_segs.args(), batch.meta, stream=ss)
+                ev_unpacked[l].record(side)
+        for l in range(L):
+            mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs)
+            ev_appended[l].record(compute)
+            if miss_segs.num_segs:
+                compute.wait_event(ev_unpacked[l])
+            if attn_events is not None:
+                a, b = attn_events[l]
+                a.record(compute)
+            mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=cs)
+            if attn_events is not None:
+                b.record(compute)
+            if evict_segs.num_segs:
+                side.wait_event(ev_appended[l])
+                mts.mts_kv_pack(cache.desc, l, offload, *evict_segs.args(), batch.meta, stream=ss)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    K = args.steps
+    if args.eager:
+        run_step = step
+    else:
+        # The step is launch-bound on the host (about ten enqueue calls per layer against
+        # tens of microseconds of GPU work), so it is captured once into a HIP graph - both
+        # streams, forked and joined by events - and replayed.
+        graph = torch.cuda.CUDAGraph()
+        ev_fork, ev_join = torch.cuda.Event(), torch.cuda.Event()
+        with torch.cuda.graph(graph, stream=compute):
+            ev_fork.record(compute)
+            side.wait_event(ev_fork)
+            step()
+            ev_join.record(side)
+            compute.wait_event(ev_join)
+        run_step = graph.replay
+        for _ in range(3):
+            run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(K):
+        run_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    # Duration of the dominant kernel: HIP events on the compute stream around every
+    # attention launch of K more (eager) steps of the same work.
+    attn_ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+               for _ in range(K)]
+    for s in range(K):
+        step(attn_ev[s])
+    torch.cuda.synchronize()
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    attn_ms = [a.elapsed_time(b) for evs in attn_ev for (a, b) in evs]
+    attn_ms_avg = float(np.mean(attn_ms))
+    kv_bytes, qo_bytes = algorithmic_bytes_per_layer(w)
+    alg_bytes = kv_bytes + qo_bytes
+    achieved = alg_bytes / (attn_ms_avg * 1e-3) / 1e9
+    flops = attention_flops_per_layer(w)
+
+    res = {
+        "metric": "new tokens/sec + KV-read HBM GB/s (% of peak) for cached-prefix incremental attention",
+        "value": N / (ms_per_step * 1e-3),
+        "unit": "new_tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic", "launch": "eager" if args.eager else "hip_graph",
+        "config": {"workload": w.name, "seed": w.seed, "users": w.batch, "layers": L, "heads": H,
+                   "head_dim": D, "page_size": w.page_size, "prefix_tokens": int(w.prefix_lens.sum()),
+                   "new_tokens": N, "miss_users": len(miss), "evict_users": len(evict),
+                   "pool_pages": w.num_pages},
+        "kv_read_gbps_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
+        "kv_read_frac_of_peak_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "attention_tflops": flops / (attn_ms_avg * 1e-3) / 1e12,
+        "roofline": {"kernel": "mts_attn_incremental (attention kernel + split-kv merge)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "bytes_per_launch": alg_bytes, "avg_launch_ms": attn_ms_avg},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(traffic_file):          # measured HBM bytes per launch, from rocprofv3 --pmc runs
+        with open(traffic_file) as f:
+            res["roofline"]["traffic"] = json.load(f).get("hbm_bytes_per_launch")
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -113,7 +113,7 @@ int32_t hip_status(hipError_t e, const char* what) {
   return fail(MTS_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-int roundup(int64_t v, int m) { return (int)((v + m - 1) / m * m); }
+int64_t roundup(int64_t v, int m) { return (v + m - 1) / m * m; }
 
 }  // namespace
 
@@ -122,37 +122,26 @@ namespace mts {
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   AttnPlan p{};
   p.use_mfma = (g.es == 2);
-  if (!p.use_mfma || b.total_new <= 0 || b.batch <= 0) {
-    p.q_tile = 16; p.q_tiles_max = 1; p.chunk = 128; p.chunks_max = 1; p.ws_bytes = 0;
-    return p;
-  }
+  p.q_tile = 16; p.q_tiles_max = 1; p.n_items = 0; p.min_tiles = 4; p.max_waves = 4;
+  if (!p.use_mfma || b.total_new <= 0 || b.batch <= 0) return p;
   const int max_new = b.max_new > 0 ? b.max_new : 1;
   p.q_tile = roundup(max_new, 16) < 64 ? roundup(max_new, 16) : 64;
   p.q_tiles_max = (max_new + p.q_tile - 1) / p.q_tile;
-  const int full = roundup(b.max_total_len > 0 ? b.max_total_len : 1, 128);
-  // (user, query tile, head) triples already in flight; split the kv axis only when they
-  // cannot fill the chip by themselves.
-  const int64_t rows = (int64_t)b.batch * p.q_tiles_max * g.H;
-  int chunk = full;
-  if (rows < 2048) {
-    // aim for a few thousand workgroups of equal kv length; never below 256 tokens, where
-    // the partial accumulators would rival the K/V traffic itself
-    int64_t kv_tokens = (int64_t)b.batch * b.max_total_len;
-    if (b.total_pages > 0 && (int64_t)b.total_pages * g.S < kv_tokens) kv_tokens = (int64_t)b.total_pages * g.S;
-    chunk = roundup(kv_tokens * g.H * p.q_tiles_max / 4096 + 1, 128);
-    if (chunk < 256) chunk = 256;
-    if (chunk > full) chunk = full;
-  }
-  if (const char* env = getenv("MTS_ATTN_CHUNK")) {
-    const int v = atoi(env);
-    if (v >= 128) chunk = roundup(v, 128) < full ? roundup(v, 128) : full;
-  }
-  p.chunk = chunk;
-  p.chunks_max = (full + chunk - 1) / chunk;
-  if (p.chunks_max < 1) p.chunks_max = 1;
-  p.ws_bytes = p.chunks_max > 1
-                   ? (int64_t)b.total_new * g.H * p.chunks_max * (g.D + 2) * (int64_t)sizeof(float)
-                   : 0;
+  const int64_t items = (int64_t)b.batch * p.q_tiles_max;
+  const int64_t tiles_upper = items * ((b.max_total_len + 31) / 32) * g.H;   // kv tiles of the call
+  if (items > 16384 || tiles_upper >= (1ll << 31)) { p.too_large = true; return p; }
+  p.n_items = (int)items;
+  // a wavefront's share is never shorter than this: below it, start-up and the partial
+  // accumulators cost more than the share itself
+  if (const char* env = getenv("MTS_ATTN_MIN_TILES")) { const int v = atoi(env); if (v >= 1) p.min_tiles = v; }
+  int64_t waves = (tiles_upper + p.min_tiles - 1) / p.min_tiles;
+  waves = (waves + 3) / 4 * 4;
+  int64_t cap = 2048;                                   // 256 CUs x 4 SIMDs x 2 wavefronts
+  if (const char* env = getenv("MTS_ATTN_MAX_WAVES")) { const int v = atoi(env); if (v >= 4) cap = v / 4 * 4; }
+  p.max_waves = (int)(waves < cap ? waves : cap);
+  if (p.max_waves < 4) p.max_waves = 4;
+  p.ws_cum_bytes = roundup((items + 1) * (int64_t)sizeof(int), 256);
+  p.ws_bytes = p.ws_cum_bytes + (int64_t)p.max_waves * 2 * p.q_tile * (g.D + 2) * (int64_t)sizeof(float);
   return p;
 }
 
@@ -238,7 +227,9 @@ int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_me
   int32_t st;
   if ((st = check_cache(cache, 0, false, &g)) != MTS_OK) return st;
   if ((st = check_meta(meta, true, false, &b)) != MTS_OK) return st;
-  return mts::plan_attention(g, b).ws_bytes;
+  const mts::AttnPlan plan = mts::plan_attention(g, b);
+  if (plan.too_large) return fail(MTS_ERR_UNSUPPORTED, "too many query tiles or kv tiles for one call");
+  return plan.ws_bytes;
 }
 
 int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
@@ -255,6 +246,9 @@ int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const v
   if (!q || !out) return fail(MTS_ERR_INVALID_ARG, "q / out is NULL");
   if (!aligned(q, 16) || !aligned(out, 16)) return fail(MTS_ERR_INVALID_ARG, "q / out is not 16-byte aligned");
   const mts::AttnPlan plan = mts::plan_attention(g, b);
+  if (plan.too_large)
+    return fail(MTS_ERR_UNSUPPORTED, "batch %d x ceil(max_new %d / 64) exceeds 16384 query tiles, or the call "
+                "has 2^31 or more kv tiles", b.batch, b.max_new);
   if (plan.ws_bytes > 0) {
     if (!workspace) return fail(MTS_ERR_WORKSPACE, "workspace is NULL but %lld bytes are needed", (long long)plan.ws_bytes);
     if (workspace_bytes < plan.ws_bytes)

@@ -1,23 +1,27 @@
 // Incremental-prefill attention on the matrix cores (Sec. 2, Eq. 6-7; Alg. 1 step 8.4),
 // bf16 inputs, fp32 logits / softmax statistics / accumulators.
 //
-// Work split.  A workgroup (4 wavefronts) owns one (user, head, query tile, kv chunk): up to
-// 64 of the user's new tokens against `chunk` consecutive kv tokens.  The 4 wavefronts take
-// the chunk's 32-token tiles round-robin, each keeping its own running (max, sum, O), and
-// combine through LDS at the end.  If the query tile has one chunk the workgroup writes the
-// output rows; otherwise it writes unnormalised partials and the merge kernel finishes them
-// (split-kv, so that a few long histories still fill 256 CUs, and every K/V byte is read
-// from HBM exactly once).
+// Schedule.  The work of one call is a single sequence of 32-token kv tiles, ordered by
+// (user, query tile, head, tile).  The launch is persistent: a fixed number of wavefronts
+// (one or two per SIMD) each take an equal, contiguous share of that sequence, so lognormal
+// history lengths cost no imbalance and every K/V byte is read from HBM exactly once.  Every
+// workgroup derives the schedule by itself from the device-resident lengths (a prefix sum in
+// LDS), so the host needs no copy of them.  A wavefront that covers a whole (query tile,
+// head) writes its output rows; where a share boundary cuts through one, the wavefronts on
+// both sides write unnormalised partials and a small merge kernel finishes those rows, in
+// wavefront order (deterministic).
 //
 // Operand flow.  Scores are computed transposed, S^T = K Q^T with v_mfma_f32_16x16x32_bf16:
-// tokens are the M rows, queries the N columns, so a lane's 4 accumulator values belong to
-// ONE query; softmax statistics are per-lane scalars and the row max needs two cross-lane
-// steps.  With the pool's K slot order, the 8 values a lane holds after the two half-tiles
+// tokens are the M rows, queries the N columns, so a lane's accumulator values belong to ONE
+// query; softmax statistics are per-lane scalars and the tile max needs two cross-lane
+// swaps.  With the pool's K slot order, the 8 values a lane holds after the two half-tiles
 // are 8 consecutive tokens, which is exactly the B fragment of O^T = V^T P^T; V is stored
 // [dim][token], so its A fragment is one 16-byte load.  Nothing is staged through LDS: each
-// 16-byte global load is already an MFMA fragment, and a wavefront's loads cover whole
-// 512-byte runs of a page.
+// 16-byte global load is already an MFMA fragment, a wavefront's loads cover whole 512-byte
+// runs of a page, and a ring of PF tiles per wavefront is kept in flight in registers.
 #include <math.h>
+
+#include <type_traits>
 
 #include "mts_internal.hpp"
 
@@ -25,329 +29,446 @@ namespace mts {
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-constexpr int kWaves = 4;
-constexpr int kTile = 32;     // kv tokens per wavefront step (two 16-token sub-blocks)
-constexpr int kPad = 4;       // LDS row padding, floats
+constexpr int kTile = 32;       // kv tokens per step (two 16-token sub-blocks)
+constexpr int kWavesPerWg = 4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-struct TilePtrs {
-  const char* sub0;   // K block base of the tile's first 16-token sub-block (this head)
-  const char* sub1;   // ... second sub-block
+// max over the 4 lanes that hold the same query (lane, lane^16, lane^32, lane^48)
+__device__ __forceinline__ float quad_row_max(float v) {
+  unsigned u = __float_as_uint(v);
+  auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  u = __float_as_uint(v);
+  auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quad_row_sum(float v) {
+  unsigned u = __float_as_uint(v);
+  auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  u = __float_as_uint(v);
+  auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// ---- schedule, shared by the attention and the merge kernel -------------------------------
+struct Item {            // one (user, query tile)
+  int tok0, n_u, P, q0, q1, tiles;   // tiles = kv tiles visible to the tile's last query
 };
 
-template <int D, int NQB>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(PoolGeom g, BatchDev b,
-                                                        const uint16_t* __restrict__ q,
-                                                        uint16_t* __restrict__ out, float c,
-                                                        int chunk, int chunks_max, int q_tiles_max,
-                                                        float* __restrict__ ws_o,
-                                                        float* __restrict__ ws_ml) {
-  constexpr int QT = 16 * NQB;       // queries per workgroup
+__device__ __forceinline__ Item load_item(const BatchDev& b, int item, int q_tiles_max, int q_tile) {
+  Item it;
+  const int u = item / q_tiles_max, qt = item % q_tiles_max;
+  it.tok0 = b.new_indptr[u];
+  it.n_u = b.new_indptr[u + 1] - it.tok0;
+  it.P = b.prefix_lens[u];
+  it.q0 = qt * q_tile;
+  it.q1 = (it.n_u < it.q0 + q_tile) ? it.n_u : (it.q0 + q_tile);
+  it.tiles = (it.q0 < it.n_u) ? (it.P + it.q1 + kTile - 1) / kTile : 0;
+  return it;
+}
+
+// share of wavefront w: [lo, hi) in global tile positions
+__device__ __forceinline__ void wave_share(int total, int num_waves, int min_tiles, int w, int* lo, int* hi) {
+  int per = (total + num_waves - 1) / num_waves;
+  if (per < min_tiles) per = min_tiles;
+  const long long l = (long long)w * per;
+  *lo = l < total ? (int)l : total;
+  *hi = (l + per) < total ? (int)(l + per) : total;
+}
+__device__ __forceinline__ int tiles_per_wave(int total, int num_waves, int min_tiles) {
+  const int per = (total + num_waves - 1) / num_waves;
+  return per < min_tiles ? min_tiles : per;
+}
+
+// largest i in [0, n) with cum[i] <= pos   (cum is non-decreasing, cum[0] = 0, pos < cum[n])
+template <typename P>
+__device__ __forceinline__ int find_item(P cum, int n, int pos) {
+  int lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cum[mid] <= pos) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <int D, int NQB, int PF>
+__global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b,
+                                                          const uint16_t* __restrict__ q,
+                                                          uint16_t* __restrict__ out, float c,
+                                                          int q_tiles_max, int n_items, int min_tiles,
+                                                          int* __restrict__ ws_cum,
+                                                          float* __restrict__ ws_o,
+                                                          float* __restrict__ ws_ml) {
+  constexpr int QT = 16 * NQB;       // queries per query tile
   constexpr int KS = D / 32;         // k-steps of Q.K
   constexpr int DB = D / 16;         // 16-dim blocks of the output
-  constexpr int LD = D + kPad;       // LDS row stride, floats
 
-  extern __shared__ float lds[];
-  float* buf0 = lds;                         // [QT][LD]
-  float* buf1 = lds + QT * LD;               // [QT][LD]
-  float* lds_m = lds + 2 * QT * LD;          // [kWaves][QT]
-  float* lds_l = lds_m + kWaves * QT;        // [2][QT]
-  float* lds_M = lds_l + 2 * QT;             // [QT]
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  extern __shared__ int lds_cum[];   // [n_items + 1] exclusive prefix of tiles * H, then 4 wave totals
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = uniform(tid >> 6);
   const int r = lane & 15, gq = lane >> 4;
   const int H = g.H, S = g.S;
 
-  const int cidx = blockIdx.x % chunks_max;
-  const int t = blockIdx.x / chunks_max;
-  const int u = t / q_tiles_max;
-  const int qt = q_tiles_max - 1 - (t % q_tiles_max);   // longest causal rows first
-  const int h = blockIdx.y;
-
-  const int tok0 = b.new_indptr[u];
-  const int n_u = b.new_indptr[u + 1] - tok0;
-  const int q0 = qt * QT;
-  if (q0 >= n_u) return;
-  const int q1 = (n_u < q0 + QT) ? n_u : (q0 + QT);
-  const int nq = q1 - q0;
-  const int nqb = (nq + 15) >> 4;
-  const int P = b.prefix_lens[u];
-  const int kv_end = P + q1;                  // keys [0, kv_end) are visible to the tile's last query
-  const int T_u = P + n_u;                    // tokens that hold data
-  const int nchunks = (kv_end + chunk - 1) / chunk;
-  if (cidx >= nchunks) return;
-  const int k0 = cidx * chunk;
-  const int k1 = (kv_end < k0 + chunk) ? kv_end : (k0 + chunk);
-  const int tile_beg = k0 / kTile;
-  const int tile_end = (k1 + kTile - 1) / kTile;
-  const int first_query_pos = P + q0;
-
-  const int pbeg = b.page_indptr[u];
-  const int npg = b.page_indptr[u + 1] - pbeg;
-  const int sub_mask = (1 << g.sub_shift) - 1;
-  const int64_t head_off = (int64_t)h * 2 * S * D * 2;      // bytes to this head's K block
-  const int64_t v_off = (int64_t)S * D * 2;                 // K block -> V block
-
-  // Q^T fragments: lane (r, gq) holds query q0+16*qb+r, dims 32*s + 8*gq .. +7.
-  bf16x8 qf[NQB][KS];
+  // ---- schedule: every workgroup computes the same prefix sum --------------------------
+  {
+    const int per_thread = (n_items + 255) / 256;
+    const int first = tid * per_thread;
+    int local = 0;
+    for (int k = 0; k < per_thread; ++k) {
+      const int item = first + k;
+      if (item < n_items) local += load_item(b, item, q_tiles_max, QT).tiles * H;
+    }
+    int incl = local;                                  // inclusive scan over the wavefront
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int i = q0 + 16 * qb + r;
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      if (i < n_u) {
-        qf[qb][s] = *reinterpret_cast<const bf16x8*>(q + ((int64_t)(tok0 + i) * H + h) * D + 32 * s + 8 * gq);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[qb][s][e] = (__bf16)0.0f;
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    int* wave_tot = lds_cum + n_items + 1;
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int base = incl - local;
+    for (int w = 0; w < wave; ++w) base += wave_tot[w];
+    for (int k = 0; k < per_thread; ++k) {
+      const int item = first + k;
+      if (item < n_items) {
+        lds_cum[item] = base;
+        base += load_item(b, item, q_tiles_max, QT).tiles * H;
       }
     }
+    if (tid == 255) lds_cum[n_items] = base;
+    __syncthreads();
+    if (blockIdx.x == 0)                               // the merge kernel reads it from here
+      for (int k = tid; k <= n_items; k += 256) ws_cum[k] = lds_cum[k];
   }
+  const int total = lds_cum[n_items];
+  const int num_waves = gridDim.x * kWavesPerWg;
+  const int wid = blockIdx.x * kWavesPerWg + wave;
+  int lo, hi;
+  wave_share(total, num_waves, min_tiles, wid, &lo, &hi);
+  if (lo >= hi) return;                                // no barrier below this line
 
-  f32x4 o[DB][NQB];
-  float m[NQB], l[NQB];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    m[qb] = -INFINITY;
-    l[qb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+  const int sub_mask = (1 << g.sub_shift) - 1;
+  const int64_t v_off = (int64_t)S * D * 2;            // K block -> V block of the same head
 
-  for (int tile = tile_beg + wave; tile < tile_end; tile += kWaves) {
-    const int tb = tile * kTile;
-    // page-table lookup for the two sub-blocks (wave-uniform)
-    const int sb0 = tile * 2, sb1 = sb0 + 1;
-    int lp0 = sb0 >> g.sub_shift, lp1 = sb1 >> g.sub_shift;
-    if (lp0 >= npg) break;
-    if (lp1 >= npg) lp1 = lp0;
-    int pg0 = b.page_indices[pbeg + lp0];
-    int pg1 = b.page_indices[pbeg + lp1];
-    if ((unsigned)pg0 >= (unsigned)g.num_pages) pg0 = 0;
-    if ((unsigned)pg1 >= (unsigned)g.num_pages) pg1 = 0;
-    const char* kb0 = g.layer_base + (int64_t)pg0 * g.page_bytes + head_off + (int64_t)(sb0 & sub_mask) * 16 * D * 2;
-    const char* kb1 = g.layer_base + (int64_t)pg1 * g.page_bytes + head_off + (int64_t)(sb1 & sub_mask) * 16 * D * 2;
+  int pos = lo;
+  int item = find_item(lds_cum, n_items, pos);
+  while (pos < hi) {
+    while (lds_cum[item + 1] <= pos) ++item;           // skips (user, query tile)s without work
+    const int u = item / q_tiles_max;
+    const Item it = load_item(b, item, q_tiles_max, QT);
+    const int tiles = uniform(it.tiles);
+    const int item_pos = lds_cum[item];
+    const int h = uniform((pos - item_pos) / tiles);
+    const int t_beg = uniform((pos - item_pos) % tiles);
+    const int pair_end = item_pos + (h + 1) * tiles;
+    const int seg_end = pair_end < hi ? pair_end : hi;
+    const int t_end = uniform(t_beg + (seg_end - pos));
+    const int tok0 = uniform(it.tok0), n_u = uniform(it.n_u), P = uniform(it.P);
+    const int q0 = uniform(it.q0), nq = uniform(it.q1 - it.q0);
+    const int nqb = (nq + 15) >> 4;
+    const int T_u = P + n_u;                           // tokens that hold data
+    const int first_query_pos = P + q0;
+    const int pbeg = uniform(b.page_indptr[u]);
+    const int npg = uniform(b.page_indptr[u + 1]) - pbeg;
+    const char* head_base = g.layer_base + (int64_t)h * 2 * S * D * 2;
 
-    // K fragments: rows 0-7 of a half-tile come from sub-block 0, rows 8-15 from sub-block 1.
-    const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
-    bf16x8 kf[2][KS];
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-        kf[hf][s] = *reinterpret_cast<const bf16x8*>(kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16);
-    // V^T fragments: lane (r, gq) holds dim 16*db + r, tokens 8*gq .. +7 of the tile.
-    const char* vl = ((gq < 2) ? kb0 : kb1) + v_off + (r * 16 + (gq & 1) * 8) * 2;
-    bf16x8 vf[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-      vf[db] = *reinterpret_cast<const bf16x8*>(vl + db * 16 * 16 * 2);
-
-    const bool masked = (tb + kTile - 1 > first_query_pos);   // some key is hidden from some query
-    if (masked && tb + kTile > T_u) {
-      // slots past the user's last token may hold anything: keep them out of P.V
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (tb + 8 * gq + e >= T_u) vf[db][e] = (__bf16)0.0f;
-    }
-
+    // Q^T fragments: lane (r, gq) holds query q0+16*qb+r, dims 32*s + 8*gq .. +7.
+    bf16x8 qf[NQB][KS];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      if (qb < nqb) {
-        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+      const int i = q0 + 16 * qb + r;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[qb][s], s0, 0, 0, 0);
-          s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[qb][s], s1, 0, 0, 0);
+      for (int s = 0; s < KS; ++s) {
+        if (i < n_u) {
+          qf[qb][s] = *reinterpret_cast<const bf16x8*>(q + ((int64_t)(tok0 + i) * H + h) * D + 32 * s + 8 * gq);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) qf[qb][s][e] = (__bf16)0.0f;
         }
-        // lane holds, for query q0+16*qb+r, keys tb + 8*gq + {0..3} (s0) and {4..7} (s1)
-        if (masked) {
-          const int qpos = first_query_pos + 16 * qb + r;
-          const int kbase = tb + 8 * gq;
+      }
+    }
+
+    f32x4 o[DB][NQB];
+    float m[NQB], l[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      m[qb] = -INFINITY;
+      l[qb] = 0.f;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // Page ids travel in a vector register: lane j holds the id of logical page 64*win + j.
+    int win = (t_beg * 2 >> g.sub_shift) >> 6;
+    auto load_window = [&](int w) -> int {
+      const int lp = w * 64 + lane;
+      return (lp < npg) ? b.page_indices[pbeg + lp] : -1;
+    };
+    int pg_cur = load_window(win);
+    int pg_next = load_window(win + 1);
+
+    bf16x8 kf[PF][2][KS];
+    bf16x8 vf[PF][DB];
+    auto issue = [&](auto buf, int tile) {            // buf is an integral_constant: register ring slot
+      constexpr int p = decltype(buf)::value;
+      const int sb0 = tile * 2, sb1 = sb0 + 1;
+      const int lp0 = sb0 >> g.sub_shift, lp1 = sb1 >> g.sub_shift;
+      if ((lp0 >> 6) != win) {                         // the load stream enters the next window
+        win = lp0 >> 6;
+        pg_cur = pg_next;
+        pg_next = load_window(win + 1);
+      }
+      int pg0 = __builtin_amdgcn_readlane(pg_cur, lp0 & 63);
+      int pg1 = __builtin_amdgcn_readlane(pg_cur, lp1 & 63);
+      if ((unsigned)pg0 >= (unsigned)g.num_pages) pg0 = 0;
+      if ((unsigned)pg1 >= (unsigned)g.num_pages) pg1 = pg0;   // also: no second page at the tail
+      const char* kb0 = head_base + (int64_t)pg0 * g.page_bytes + (int64_t)(sb0 & sub_mask) * 16 * D * 2;
+      const char* kb1 = head_base + (int64_t)pg1 * g.page_bytes + (int64_t)(sb1 & sub_mask) * 16 * D * 2;
+      // K fragments: rows 0-7 of a half-tile come from sub-block 0, rows 8-15 from sub-block 1.
+      const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+          kf[p][hf][s] = *reinterpret_cast<const bf16x8*>(kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16);
+      // V^T fragments: lane (r, gq) holds dim 16*db + r, tokens 8*gq .. +7 of the tile.
+      const char* vl = ((gq < 2) ? kb0 : kb1) + v_off + (r * 16 + (gq & 1) * 8) * 2;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        vf[p][db] = *reinterpret_cast<const bf16x8*>(vl + db * 16 * 16 * 2);
+    };
+
+    auto compute = [&](auto buf, int tile) {
+      constexpr int p = decltype(buf)::value;
+      const int tb = tile * kTile;
+      const bool masked = (tb + kTile - 1 > first_query_pos);   // some key hidden from some query
+      if (masked && tb + kTile > T_u) {
+        // slots past the user's last token may hold anything: keep them out of P.V
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (tb + 8 * gq + e >= T_u) vf[p][db][e] = (__bf16)0.0f;
+      }
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        if (qb < nqb) {
+          f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 0; s < KS; ++s) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][0][s], qf[qb][s], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][1][s], qf[qb][s], s1, 0, 0, 0);
+          }
+          // lane holds, for query q0+16*qb+r, keys tb + 8*gq + {0..3} (s0) and {4..7} (s1)
+          if (masked) {
+            const int qpos = first_query_pos + 16 * qb + r;
+            const int kbase = tb + 8 * gq;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (kbase + e > qpos) s0[e] = -INFINITY;
+              if (kbase + 4 + e > qpos) s1[e] = -INFINITY;
+            }
+          }
+          float tmax = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                             fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+          tmax = quad_row_max(tmax);
+          const float m_new = fmaxf(m[qb], tmax);
+          const float mref = (m_new == -INFINITY) ? 0.f : m_new;
+          const float alpha = fast_exp2((m[qb] - mref) * c);
+          const float mc = mref * c;
+          float psum = 0.f;
+          bf16x8 pf;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            if (kbase + e > qpos) s0[e] = -INFINITY;
-            if (kbase + 4 + e > qpos) s1[e] = -INFINITY;
+            const float p0 = fast_exp2(fmaf(s0[e], c, -mc));
+            const float p1 = fast_exp2(fmaf(s1[e], c, -mc));
+            psum += p0 + p1;
+            pf[e] = (__bf16)p0;
+            pf[4 + e] = (__bf16)p1;
+          }
+          l[qb] = l[qb] * alpha + psum;
+          m[qb] = m_new;
+#pragma unroll
+          for (int db = 0; db < DB; ++db) {
+            o[db][qb] *= alpha;
+            o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][db], pf, o[db][qb], 0, 0, 0);
           }
         }
-        float tmax = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
-                           fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m[qb], tmax);
-        const float mref = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2((m[qb] - mref) * c);
-        const float mc = mref * c;
-        float psum = 0.f;
-        bf16x8 pf;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p0 = fast_exp2(fmaf(s0[e], c, -mc));
-          const float p1 = fast_exp2(fmaf(s1[e], c, -mc));
-          psum += p0 + p1;
-          pf[e] = (__bf16)p0;
-          pf[4 + e] = (__bf16)p1;
+      }
+    };
+
+    // software pipeline: PF tiles in flight per wavefront
+    {
+      // The ring is written out with integral_constant slots so that every register array is
+      // indexed by constants only.
+      auto prologue = [&](auto pc) {
+        constexpr int p = decltype(pc)::value;
+        if (t_beg + p < t_end) issue(pc, t_beg + p);
+      };
+      auto phase = [&](auto pc, int base) {
+        constexpr int p = decltype(pc)::value;
+        const int tile = base + p;
+        if (tile < t_end) {
+          compute(pc, tile);
+          if (tile + PF < t_end) issue(pc, tile + PF);
         }
-        l[qb] = l[qb] * alpha + psum;
-        m[qb] = m_new;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          o[db][qb] *= alpha;
-          o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, o[db][qb], 0, 0, 0);
-        }
+      };
+      prologue(std::integral_constant<int, 0>{});
+      if constexpr (PF > 1) prologue(std::integral_constant<int, 1>{});
+      if constexpr (PF > 2) prologue(std::integral_constant<int, 2>{});
+      if constexpr (PF > 3) prologue(std::integral_constant<int, 3>{});
+      for (int base = t_beg; base < t_end; base += PF) {
+        phase(std::integral_constant<int, 0>{}, base);
+        if constexpr (PF > 1) phase(std::integral_constant<int, 1>{}, base);
+        if constexpr (PF > 2) phase(std::integral_constant<int, 2>{}, base);
+        if constexpr (PF > 3) phase(std::integral_constant<int, 3>{}, base);
       }
     }
-  }
 
-  // ---- combine the 4 wavefronts (same queries, disjoint keys) ----
+    // ---- finish the segment ----
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    l[qb] += __shfl_xor(l[qb], 16);
-    l[qb] += __shfl_xor(l[qb], 32);
-    if (gq == 0) lds_m[wave * QT + 16 * qb + r] = m[qb];
-  }
-  __syncthreads();
+    for (int qb = 0; qb < NQB; ++qb) l[qb] = quad_row_sum(l[qb]);
+    const bool complete = (t_beg == 0) && (t_end == tiles);
+    if (complete) {
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int qi = 16 * qb + r;
-    float M = lds_m[qi];
+      for (int qb = 0; qb < NQB; ++qb) {
+        const int qi = 16 * qb + r;
+        if (qi < nq) {
+          const float inv = 1.0f / l[qb];
+          uint16_t* orow = out + ((int64_t)(tok0 + q0 + qi) * H + h) * D + 4 * gq;
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, lds_m[w * QT + qi]);
-    const float mref = (M == -INFINITY) ? 0.f : M;
-    const float f = fast_exp2((m[qb] - mref) * c);      // 0 for a wavefront that saw no key
-    l[qb] *= f;
+          for (int db = 0; db < DB; ++db) {
+            bf16x4 ob;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) o[db][qb] *= f;
-    if (wave == 0 && gq == 0) lds_M[qi] = M;
-  }
-  if (wave < 2) {
-    float* buf = wave ? buf1 : buf0;
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const int qi = 16 * qb + r;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-        *reinterpret_cast<f32x4*>(buf + qi * LD + 16 * db + 4 * gq) = o[db][qb];
-      if (gq == 0) lds_l[wave * QT + qi] = l[qb];
-    }
-  }
-  __syncthreads();
-  if (wave >= 2) {
-    float* buf = (wave == 3) ? buf1 : buf0;
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const int qi = 16 * qb + r;
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        f32x4* p = reinterpret_cast<f32x4*>(buf + qi * LD + 16 * db + 4 * gq);
-        *p = *p + o[db][qb];
+            for (int k = 0; k < 4; ++k) ob[k] = (__bf16)(o[db][qb][k] * inv);
+            *reinterpret_cast<bf16x4*>(orow + 16 * db) = ob;
+          }
+        }
       }
-      if (gq == 0) lds_l[(wave - 2) * QT + qi] += l[qb];
-    }
-  }
-  __syncthreads();
-
-  // ---- write output rows (single chunk) or partials (split kv) ----
-  constexpr int D4 = D / 4;
-  for (int e = threadIdx.x; e < nq * D4; e += 256) {
-    const int qi = e / D4, d4 = e % D4;
-    const f32x4 a = *reinterpret_cast<const f32x4*>(buf0 + qi * LD + 4 * d4);
-    const f32x4 bb = *reinterpret_cast<const f32x4*>(buf1 + qi * LD + 4 * d4);
-    const f32x4 acc = a + bb;
-    const float lsum = lds_l[qi] + lds_l[QT + qi];
-    const int64_t row = (int64_t)(tok0 + q0 + qi) * H + h;
-    if (nchunks == 1) {
-      const float inv = 1.0f / lsum;
-      bf16x4 ob;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) ob[k] = (__bf16)(acc[k] * inv);
-      *reinterpret_cast<bf16x4*>(out + row * D + 4 * d4) = ob;
     } else {
-      const int64_t slot = row * chunks_max + cidx;
-      *reinterpret_cast<f32x4*>(ws_o + slot * D + 4 * d4) = acc;
-      if (d4 == 0) {
-        ws_ml[slot * 2] = lds_M[qi];
-        ws_ml[slot * 2 + 1] = lsum;
+      const int slot = (pos == lo) ? 0 : 1;            // leading or trailing piece of this share
+      const int64_t prow = ((int64_t)wid * 2 + slot) * QT;
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const int qi = 16 * qb + r;
+        if (qi < nq) {
+          float* po = ws_o + (prow + qi) * D + 4 * gq;
+#pragma unroll
+          for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db) = o[db][qb];
+          if (gq == 0) {
+            ws_ml[(prow + qi) * 2] = m[qb];
+            ws_ml[(prow + qi) * 2 + 1] = l[qb];
+          }
+        }
       }
     }
+    pos = seg_end;
   }
 }
 
-// Finish the query tiles that were split over several kv chunks: a numerically safe
-// weighted sum of the chunk partials, in chunk order (deterministic).
+// Finishes the (query tile, head)s that a share boundary cut: workgroup w looks at the pair
+// that holds the last tile of share w; if that pair starts inside share w and continues past
+// it, w merges the partials of all shares that touch it, in share order.
 template <int D>
-__global__ __launch_bounds__(D) void attn_merge_kernel(BatchDev b, int H, uint16_t* __restrict__ out,
-                                                       float c, int chunk, int chunks_max, int q_tile,
-                                                       const float* __restrict__ ws_o,
-                                                       const float* __restrict__ ws_ml) {
-  const int tok = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
-  int lo = 0, hi = b.batch;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (b.new_indptr[mid] <= tok) lo = mid; else hi = mid;
+__global__ __launch_bounds__(256) void attn_merge_kernel(BatchDev b, int H, uint16_t* __restrict__ out,
+                                                         float c, int q_tile, int q_tiles_max, int n_items,
+                                                         int min_tiles, int num_waves,
+                                                         const int* __restrict__ ws_cum,
+                                                         const float* __restrict__ ws_o,
+                                                         const float* __restrict__ ws_ml) {
+  const int w = blockIdx.x;
+  const int total = ws_cum[n_items];
+  int lo, hi;
+  wave_share(total, num_waves, min_tiles, w, &lo, &hi);
+  if (lo >= hi) return;
+  const int item = find_item(ws_cum, n_items, hi - 1);
+  const Item it = load_item(b, item, q_tiles_max, q_tile);
+  const int item_pos = ws_cum[item];
+  const int h = (hi - 1 - item_pos) / it.tiles;
+  const int pair_beg = item_pos + h * it.tiles;
+  const int pair_end = pair_beg + it.tiles;
+  if (!(pair_end > hi && pair_beg >= lo)) return;      // not cut, or another share owns the merge
+  const int per = tiles_per_wave(total, num_waves, min_tiles);
+  const int w_last = (pair_end - 1) / per;
+  const int nq = it.q1 - it.q0;
+  constexpr int D4 = D / 4;
+  for (int e = threadIdx.x; e < nq * D4; e += blockDim.x) {
+    const int qi = e / D4, d4 = e % D4;
+    float M = -INFINITY;
+    for (int ww = w; ww <= w_last; ++ww) {
+      const int slot = ((long long)ww * per >= pair_beg) ? 0 : 1;
+      M = fmaxf(M, ws_ml[(((int64_t)ww * 2 + slot) * q_tile + qi) * 2]);
+    }
+    f32x4 num = {0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+    for (int ww = w; ww <= w_last; ++ww) {
+      const int slot = ((long long)ww * per >= pair_beg) ? 0 : 1;
+      const int64_t prow = ((int64_t)ww * 2 + slot) * q_tile + qi;
+      const float wgt = fast_exp2((ws_ml[prow * 2] - M) * c);   // a share that saw no visible key has max -inf
+      const f32x4 part = *reinterpret_cast<const f32x4*>(ws_o + prow * D + 4 * d4);
+      num += part * wgt;
+      den = fmaf(wgt, ws_ml[prow * 2 + 1], den);
+    }
+    const float inv = 1.0f / den;
+    bf16x4 ob;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) ob[k] = (__bf16)(num[k] * inv);
+    *reinterpret_cast<bf16x4*>(out + ((int64_t)(it.tok0 + it.q0 + qi) * H + h) * D + 4 * d4) = ob;
   }
-  const int u = lo;
-  const int tok0 = b.new_indptr[u];
-  const int n_u = b.new_indptr[u + 1] - tok0;
-  const int i = tok - tok0;
-  const int q0 = (i / q_tile) * q_tile;
-  const int q1 = (n_u < q0 + q_tile) ? n_u : (q0 + q_tile);
-  const int kv_end = b.prefix_lens[u] + q1;
-  const int nchunks = (kv_end + chunk - 1) / chunk;
-  if (nchunks <= 1) return;                       // written by the attention kernel itself
-  const int64_t row = (int64_t)tok * H + h;
-  const float* ml = ws_ml + row * chunks_max * 2;
-  float M = -INFINITY;
-  for (int k = 0; k < nchunks; ++k) M = fmaxf(M, ml[2 * k]);
-  float num = 0.f, den = 0.f;
-  for (int k = 0; k < nchunks; ++k) {
-    const float w = fast_exp2((ml[2 * k] - M) * c);   // chunks hidden from this query have max = -inf
-    num = fmaf(w, ws_o[(row * chunks_max + k) * D + d], num);
-    den = fmaf(w, ml[2 * k + 1], den);
-  }
-  const float v = num / den;
-  uint32_t bits = __float_as_uint(v);
-  bits += 0x7fffu + ((bits >> 16) & 1u);
-  out[row * D + d] = (uint16_t)(bits >> 16);
 }
 
-template <int D, int NQB>
+template <int D, int NQB, int PF>
 hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
-                      const BatchDev& b, float c, float* ws_o, float* ws_ml, hipStream_t stream) {
-  constexpr int QT = 16 * NQB;
-  const size_t lds_bytes = sizeof(float) * (2 * QT * (D + kPad) + kWaves * QT + 2 * QT + QT);
-  auto kern = attn_mfma_kernel<D, NQB>;
-  if (lds_bytes > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                      const BatchDev& b, float c, void* workspace, hipStream_t stream) {
+  auto kern = attn_stream_kernel<D, NQB, PF>;
+  const size_t lds_bytes = sizeof(int) * (plan.n_items + 1 + kWavesPerWg);
+  static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
+  if (wgs_per_cu == 0) {
+    int dev = 0, n = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, 256, 16 * 1024);
     if (e != hipSuccess) return e;
+    num_cus = cus > 0 ? cus : 256;
+    wgs_per_cu = n < 1 ? 1 : (n > 2 ? 2 : n);
   }
-  const int64_t gx = (int64_t)b.batch * plan.q_tiles_max * plan.chunks_max;
-  dim3 grid((unsigned)gx, (unsigned)g.H, 1), block(256, 1, 1);
-  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, g, b, q, out, c, plan.chunk,
-                     plan.chunks_max, plan.q_tiles_max, ws_o, ws_ml);
+  int wgs = num_cus * wgs_per_cu;
+  if (wgs * kWavesPerWg > plan.max_waves) wgs = plan.max_waves / kWavesPerWg;
+  if (wgs < 1) wgs = 1;
+  char* ws = static_cast<char*>(workspace);
+  int* ws_cum = reinterpret_cast<int*>(ws);
+  float* ws_o = reinterpret_cast<float*>(ws + plan.ws_cum_bytes);
+  float* ws_ml = ws_o + (int64_t)plan.max_waves * 2 * plan.q_tile * g.D;
+  hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, out, c, plan.q_tiles_max,
+                     plan.n_items, plan.min_tiles, ws_cum, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || plan.chunks_max <= 1) return e;
-  dim3 mgrid((unsigned)b.total_new, (unsigned)g.H, 1), mblock(D, 1, 1);
-  hipLaunchKernelGGL(attn_merge_kernel<D>, mgrid, mblock, 0, stream, b, g.H, out, c, plan.chunk,
-                     plan.chunks_max, plan.q_tile, ws_o, ws_ml);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(wgs * kWavesPerWg), dim3(256), 0, stream, b, g.H, out, c,
+                     plan.q_tile, plan.q_tiles_max, plan.n_items, plan.min_tiles, wgs * kWavesPerWg,
+                     ws_cum, ws_o, ws_ml);
   return hipGetLastError();
 }
 
+// PF (tiles in flight per wavefront) is bounded by the register file: the ring holds
+// PF * D / 2 registers per lane beside the Q fragments and the output accumulators.
 template <int D>
 hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
-                    const BatchDev& b, float c, float* ws_o, float* ws_ml, hipStream_t stream) {
+                    const BatchDev& b, float c, void* ws, hipStream_t stream) {
+  constexpr int PF_SMALL = (D == 128) ? 3 : 4;   // up to 32 queries per tile
+  constexpr int PF_LARGE = (D == 128) ? 2 : 4;   // 48 or 64 queries per tile
   switch (plan.q_tile / 16) {
-    case 1: return launch_one<D, 1>(g, plan, q, out, b, c, ws_o, ws_ml, stream);
-    case 2: return launch_one<D, 2>(g, plan, q, out, b, c, ws_o, ws_ml, stream);
-    case 3: return launch_one<D, 3>(g, plan, q, out, b, c, ws_o, ws_ml, stream);
-    default: return launch_one<D, 4>(g, plan, q, out, b, c, ws_o, ws_ml, stream);
+    case 1: return launch_one<D, 1, PF_SMALL>(g, plan, q, out, b, c, ws, stream);
+    case 2: return launch_one<D, 2, PF_SMALL>(g, plan, q, out, b, c, ws, stream);
+    case 3: return launch_one<D, 3, PF_LARGE>(g, plan, q, out, b, c, ws, stream);
+    default: return launch_one<D, 4, PF_LARGE>(g, plan, q, out, b, c, ws, stream);
   }
 }
 
@@ -357,14 +478,12 @@ hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void*
                             const BatchDev& b, float sm_scale, void* workspace, hipStream_t stream) {
   if (b.total_new <= 0 || b.batch <= 0) return hipSuccess;
   const float c = sm_scale * 1.4426950408889634f;     // logits are exponentiated in base 2
-  float* ws_o = reinterpret_cast<float*>(workspace);
-  float* ws_ml = ws_o ? ws_o + (int64_t)b.total_new * g.H * plan.chunks_max * g.D : nullptr;
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(q);
   uint16_t* op = reinterpret_cast<uint16_t*>(out);
   switch (g.D) {
-    case 32: return launch_d<32>(g, plan, qp, op, b, c, ws_o, ws_ml, stream);
-    case 64: return launch_d<64>(g, plan, qp, op, b, c, ws_o, ws_ml, stream);
-    case 128: return launch_d<128>(g, plan, qp, op, b, c, ws_o, ws_ml, stream);
+    case 32: return launch_d<32>(g, plan, qp, op, b, c, workspace, stream);
+    case 64: return launch_d<64>(g, plan, qp, op, b, c, workspace, stream);
+    case 128: return launch_d<128>(g, plan, qp, op, b, c, workspace, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -38,11 +38,14 @@ hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new
 // Shape plan of one attention call: computed on the host from the scalar bounds only.
 struct AttnPlan {
   bool    use_mfma;      // bf16 matrix-core kernel, else the plain fp32-accumulate kernel
-  int32_t q_tile;        // queries per workgroup (multiple of 16, <= 64)
+  bool    too_large;     // more (user, query tile) items than the schedule can hold
+  int32_t q_tile;        // queries per query tile (multiple of 16, <= 64)
   int32_t q_tiles_max;   // ceil(max_new / q_tile)
-  int32_t chunk;         // kv tokens per workgroup (multiple of 128)
-  int32_t chunks_max;    // ceil(max_total_len / chunk)
-  int64_t ws_bytes;      // partial accumulators + softmax statistics
+  int32_t n_items;       // batch * q_tiles_max
+  int32_t min_tiles;     // least kv tiles a wavefront's share may hold
+  int32_t max_waves;     // most wavefronts the launch may use (sizes the partial buffers)
+  int64_t ws_cum_bytes;  // schedule prefix sums at the start of the workspace
+  int64_t ws_bytes;      // whole workspace
 };
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b);
 

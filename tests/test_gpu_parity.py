@@ -106,15 +106,26 @@ def test_unpack_append_pool_image_and_pack(name):
         assert np.array_equal(step.pool_image(l), G.expected_pool_image(w, store, l, FILL))
 
 
+SCHEDULES = {
+    "default": {},
+    # one kv tile per wavefront: every (query tile, head) longer than 32 keys is cut and merged
+    "one_tile_shares": {"MTS_ATTN_MIN_TILES": "1"},
+    # a single workgroup: each wavefront walks through several (user, head) segments
+    "four_waves": {"MTS_ATTN_MAX_WAVES": "4", "MTS_ATTN_MIN_TILES": "1"},
+    "odd_shares": {"MTS_ATTN_MIN_TILES": "3", "MTS_ATTN_MAX_WAVES": "28"},
+}
+
+
 @pytest.mark.parametrize("name", list(CASES))
-@pytest.mark.parametrize("chunk_env", [None, "128"])
-def test_attention_small(name, chunk_env, monkeypatch):
-    """Element by element against the oracle; the second run forces the smallest kv chunk so
-    that the split-kv partials and the merge kernel are exercised on short sequences too."""
+@pytest.mark.parametrize("schedule", list(SCHEDULES))
+def test_attention_small(name, schedule, monkeypatch):
+    """Element by element against the oracle, under several work schedules: share boundaries
+    that cut through (query tile, head)s exercise the partial accumulators and the merge
+    kernel; shares that span several users exercise the segment loop."""
     G = _harness()
     w = _case(name)
-    if chunk_env:
-        monkeypatch.setenv("MTS_ATTN_CHUNK", chunk_env)
+    for k, v in SCHEDULES[schedule].items():
+        monkeypatch.setenv(k, v)
     data = draw_step_data(w)
     step = G.GpuStep(w, fill_byte=FILL)
     store = _oracle_store(w, data)
