@@ -25,6 +25,24 @@
 
 #include "mts_internal.hpp"
 
+#ifndef MTS_DIAG
+#define MTS_DIAG 0
+#endif
+
+#if MTS_DIAG == 6
+__device__ long long g_mts_diag[16 * 128];
+extern "C" int mts_diag_dump(long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_mts_diag), sizeof(g_mts_diag));
+}
+#define DIAG_STAMP()                                                                  \
+  do {                                                                                \
+    if ((wid & 63) == 0 && lane == 0 && diag_n < 128) g_mts_diag[(wid >> 6) * 128 + diag_n] = wall_clock64(); \
+    ++diag_n;                                                                         \
+  } while (0)
+#else
+#define DIAG_STAMP() do {} while (0)
+#endif
+
 namespace mts {
 namespace {
 
@@ -47,15 +65,6 @@ __device__ __forceinline__ float quad_row_max(float v) {
   auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
-__device__ __forceinline__ float quad_row_sum(float v) {
-  unsigned u = __float_as_uint(v);
-  auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-  u = __float_as_uint(v);
-  auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
-}
-
 // ---- schedule, shared by the attention and the merge kernel -------------------------------
 struct Item {            // one (user, query tile)
   int tok0, n_u, P, q0, q1, tiles;   // tiles = kv tiles visible to the tile's last query
@@ -115,6 +124,11 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
   const int wave = uniform(tid >> 6);
   const int r = lane & 15, gq = lane >> 4;
   const int H = g.H, S = g.S;
+#if MTS_DIAG == 6
+  int diag_n = 0;
+  const int wid_early = blockIdx.x * kWavesPerWg + wave;
+  { const int wid = wid_early; DIAG_STAMP(); }
+#endif
 
   // ---- schedule: every workgroup computes the same prefix sum --------------------------
   {
@@ -154,9 +168,13 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
   int lo, hi;
   wave_share(total, num_waves, min_tiles, wid, &lo, &hi);
   if (lo >= hi) return;                                // no barrier below this line
+  DIAG_STAMP();
 
   const int sub_mask = (1 << g.sub_shift) - 1;
   const int64_t v_off = (int64_t)S * D * 2;            // K block -> V block of the same head
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
   int pos = lo;
   int item = find_item(lds_cum, n_items, pos);
@@ -197,41 +215,50 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
     }
 
     f32x4 o[DB][NQB];
-    float m[NQB], l[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      m[qb] = -INFINITY;
-      l[qb] = 0.f;
-#pragma unroll
-      for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    f32x4 lacc[NQB];                 // softmax denominators (all 4 entries of a lane are equal)
+    float m[NQB];                    // reference max of the accumulators, raw logit units
+    float mcq[NQB];                  // the same reference, scaled for the base-2 exponent
 
-    // Page ids travel in a vector register: lane j holds the id of logical page 64*win + j.
-    int win = (t_beg * 2 >> g.sub_shift) >> 6;
-    auto load_window = [&](int w) -> int {
-      const int lp = w * 64 + lane;
-      return (lp < npg) ? b.page_indices[pbeg + lp] : -1;
+    // Page ids come through scalar loads (their counter is separate from the vector-memory
+    // one, so they never force a wait on K/V data in flight).  Ring slot p keeps the ids of
+    // the NEXT tile it will load, requested one ring revolution earlier.
+    const int last_tile = t_end - 1;
+    int idr0[PF], idr1[PF];
+    auto page_ids = [&](int tile, int& id0, int& id1) {
+      const int tl = tile < last_tile ? tile : last_tile;        // past the end: repeat the last tile
+      int lp0 = (tl * 2) >> g.sub_shift, lp1 = (tl * 2 + 1) >> g.sub_shift;
+      if (lp1 >= npg) lp1 = lp0;                                 // no second page at the tail
+      if (lp0 >= npg) lp0 = lp1 = 0;                             // metadata out of range: stay in bounds
+      id0 = npg > 0 ? b.page_indices[pbeg + lp0] : 0;
+      id1 = npg > 0 ? b.page_indices[pbeg + lp1] : 0;
     };
-    int pg_cur = load_window(win);
-    int pg_next = load_window(win + 1);
+    auto tile_bases = [&](int tile, int id0, int id1, const char*& kb0, const char*& kb1) {
+#if MTS_DIAG == 1
+      tile = t_beg;                                    // diagnostic: every load hits the same tile
+#endif
+      const int tl = tile < last_tile ? tile : last_tile;
+      const int sb0 = tl * 2, sb1 = sb0 + 1;
+      if ((unsigned)id0 >= (unsigned)g.num_pages) id0 = 0;
+      if ((unsigned)id1 >= (unsigned)g.num_pages) id1 = 0;
+      kb0 = head_base + (int64_t)id0 * g.page_bytes + (int64_t)(sb0 & sub_mask) * 16 * D * 2;
+      kb1 = head_base + (int64_t)id1 * g.page_bytes + (int64_t)(sb1 & sub_mask) * 16 * D * 2;
+    };
 
     bf16x8 kf[PF][2][KS];
     bf16x8 vf[PF][DB];
+    // Loads tile `tile` (clamped to the segment's last tile, so that the loads of the steady
+    // state are unconditional and the hardware's in-order load counter can be waited on
+    // exactly) into ring slot p, then requests the ids of the tile this slot loads next.
     auto issue = [&](auto buf, int tile) {            // buf is an integral_constant: register ring slot
       constexpr int p = decltype(buf)::value;
-      const int sb0 = tile * 2, sb1 = sb0 + 1;
-      const int lp0 = sb0 >> g.sub_shift, lp1 = sb1 >> g.sub_shift;
-      if ((lp0 >> 6) != win) {                         // the load stream enters the next window
-        win = lp0 >> 6;
-        pg_cur = pg_next;
-        pg_next = load_window(win + 1);
-      }
-      int pg0 = __builtin_amdgcn_readlane(pg_cur, lp0 & 63);
-      int pg1 = __builtin_amdgcn_readlane(pg_cur, lp1 & 63);
-      if ((unsigned)pg0 >= (unsigned)g.num_pages) pg0 = 0;
-      if ((unsigned)pg1 >= (unsigned)g.num_pages) pg1 = pg0;   // also: no second page at the tail
-      const char* kb0 = head_base + (int64_t)pg0 * g.page_bytes + (int64_t)(sb0 & sub_mask) * 16 * D * 2;
-      const char* kb1 = head_base + (int64_t)pg1 * g.page_bytes + (int64_t)(sb1 & sub_mask) * 16 * D * 2;
+#if MTS_DIAG == 4
+      if (tile >= t_beg + PF) return;                  // diagnostic: no loads after the prologue
+#endif
+#if MTS_DIAG == 5
+      if (tile >= t_beg + PF) { page_ids(tile + PF, idr0[p], idr1[p]); return; }   // only the id loads
+#endif
+      const char *kb0, *kb1;
+      tile_bases(tile, idr0[p], idr1[p], kb0, kb1);
       // K fragments: rows 0-7 of a half-tile come from sub-block 0, rows 8-15 from sub-block 1.
       const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
 #pragma unroll
@@ -244,98 +271,206 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
 #pragma unroll
       for (int db = 0; db < DB; ++db)
         vf[p][db] = *reinterpret_cast<const bf16x8*>(vl + db * 16 * 16 * 2);
+      page_ids(tile + PF, idr0[p], idr1[p]);
     };
 
-    auto compute = [&](auto buf, int tile) {
+    // S^T of query block qb against the K fragments of ring slot p.  The lane holds, for query
+    // q0+16*qb+r, keys tb + 8*gq + {0..3} (s0) and {4..7} (s1); with `masked`, keys the query
+    // must not see (causal order among the new tokens) are set to -inf.
+    auto scores = [&](auto buf, int qb, int tb, bool masked, f32x4& s0, f32x4& s1) {
+      constexpr int p = decltype(buf)::value;
+      s0 = f32x4{0.f, 0.f, 0.f, 0.f};
+      s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][0][s], qf[qb][s], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][1][s], qf[qb][s], s1, 0, 0, 0);
+      }
+      if (masked) {
+        const int qpos = first_query_pos + 16 * qb + r;
+        const int kbase = tb + 8 * gq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (kbase + e > qpos) s0[e] = -INFINITY;
+          if (kbase + 4 + e > qpos) s1[e] = -INFINITY;
+        }
+      }
+    };
+    auto max8 = [](const f32x4& s0, const f32x4& s1) {
+      return fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                   fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+    };
+
+    // One tile against NQ query blocks (NQ a compile-time constant: no branch between the
+    // blocks).  The reference max is fixed for the whole segment, so nothing is ever rescaled:
+    // softmax is shift-invariant, and weights above 1 are as exact in bf16 / fp32 as weights
+    // below 1.  TAIL adds what only the causal tail needs: the mask, and zeroing of V slots past
+    // the user's last token (they may hold anything).
+    auto tile_step = [&](auto nq_c, auto tail_c, auto buf, int tile) {
+      constexpr int NQ = decltype(nq_c)::value;
+      constexpr bool TAIL = decltype(tail_c)::value;
       constexpr int p = decltype(buf)::value;
       const int tb = tile * kTile;
-      const bool masked = (tb + kTile - 1 > first_query_pos);   // some key hidden from some query
-      if (masked && tb + kTile > T_u) {
-        // slots past the user's last token may hold anything: keep them out of P.V
+      bool masked = false;
+      if constexpr (TAIL) {
+        masked = (tb + kTile - 1 > first_query_pos);     // some key hidden from some query
+        if (masked && tb + kTile > T_u) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+          for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (tb + 8 * gq + e >= T_u) vf[p][db][e] = (__bf16)0.0f;
+            for (int e = 0; e < 8; ++e)
+              if (tb + 8 * gq + e >= T_u) vf[p][db][e] = (__bf16)0.0f;
+        }
       }
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        if (qb < nqb) {
-          f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+      for (int qb = 0; qb < NQ; ++qb) {
+        f32x4 s0, s1;
+        scores(buf, qb, tb, masked, s0, s1);
+        bf16x8 pf;
 #pragma unroll
-          for (int s = 0; s < KS; ++s) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][0][s], qf[qb][s], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][1][s], qf[qb][s], s1, 0, 0, 0);
-          }
-          // lane holds, for query q0+16*qb+r, keys tb + 8*gq + {0..3} (s0) and {4..7} (s1)
-          if (masked) {
-            const int qpos = first_query_pos + 16 * qb + r;
-            const int kbase = tb + 8 * gq;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              if (kbase + e > qpos) s0[e] = -INFINITY;
-              if (kbase + 4 + e > qpos) s1[e] = -INFINITY;
-            }
-          }
-          float tmax = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
-                             fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-          tmax = quad_row_max(tmax);
-          const float m_new = fmaxf(m[qb], tmax);
-          const float mref = (m_new == -INFINITY) ? 0.f : m_new;
-          const float alpha = fast_exp2((m[qb] - mref) * c);
-          const float mc = mref * c;
-          float psum = 0.f;
-          bf16x8 pf;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p0 = fast_exp2(fmaf(s0[e], c, -mc));
-            const float p1 = fast_exp2(fmaf(s1[e], c, -mc));
-            psum += p0 + p1;
-            pf[e] = (__bf16)p0;
-            pf[4 + e] = (__bf16)p1;
-          }
-          l[qb] = l[qb] * alpha + psum;
-          m[qb] = m_new;
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            o[db][qb] *= alpha;
-            o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][db], pf, o[db][qb], 0, 0, 0);
-          }
+        for (int e = 0; e < 4; ++e) {
+          pf[e] = (__bf16)fast_exp2(fmaf(s0[e], c, -mcq[qb]));
+          pf[4 + e] = (__bf16)fast_exp2(fmaf(s1[e], c, -mcq[qb]));
         }
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][db], pf, o[db][qb], 0, 0, 0);
+        // row sums of the (rounded) weights on the matrix core: every row of ones . P^T
+        lacc[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf, lacc[qb], 0, 0, 0);
       }
     };
 
-    // software pipeline: PF tiles in flight per wavefront
-    {
-      // The ring is written out with integral_constant slots so that every register array is
-      // indexed by constants only.
-      auto prologue = [&](auto pc) {
-        constexpr int p = decltype(pc)::value;
-        if (t_beg + p < t_end) issue(pc, t_beg + p);
-      };
-      auto phase = [&](auto pc, int base) {
-        constexpr int p = decltype(pc)::value;
-        const int tile = base + p;
-        if (tile < t_end) {
-          compute(pc, tile);
-          if (tile + PF < t_end) issue(pc, tile + PF);
+    // Exact running max of every query over the whole segment (K only, no pipelining): used
+    // when the first tile's max turned out to be too low a reference.
+    auto exact_max = [&](auto nq_c) {
+      constexpr int NQ = decltype(nq_c)::value;
+      float mx[NQ];
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) mx[qb] = -INFINITY;
+      for (int tile = t_beg; tile < t_end; ++tile) {
+        int id0, id1;
+        page_ids(tile, id0, id1);
+        const char *kb0, *kb1;
+        tile_bases(tile, id0, id1, kb0, kb1);
+        const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
+        const int tb = tile * kTile;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int s = 0; s < KS; ++s)
+            kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16);
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) {
+          f32x4 s0, s1;
+          scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > first_query_pos, s0, s1);
+          mx[qb] = fmaxf(mx[qb], max8(s0, s1));
         }
-      };
-      prologue(std::integral_constant<int, 0>{});
-      if constexpr (PF > 1) prologue(std::integral_constant<int, 1>{});
-      if constexpr (PF > 2) prologue(std::integral_constant<int, 2>{});
-      if constexpr (PF > 3) prologue(std::integral_constant<int, 3>{});
-      for (int base = t_beg; base < t_end; base += PF) {
-        phase(std::integral_constant<int, 0>{}, base);
-        if constexpr (PF > 1) phase(std::integral_constant<int, 1>{}, base);
-        if constexpr (PF > 2) phase(std::integral_constant<int, 2>{}, base);
-        if constexpr (PF > 3) phase(std::integral_constant<int, 3>{}, base);
       }
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) {
+        m[qb] = quad_row_max(mx[qb]);
+        mcq[qb] = (m[qb] == -INFINITY ? 0.f : m[qb]) * c;
+      }
+    };
+
+    // tiles [0, fast_stop) hide no key from any query of this tile
+    int fast_stop = (first_query_pos + 1) / kTile;
+    if (fast_stop > t_end) fast_stop = t_end;
+
+    // The whole segment for NQ query blocks.  Ring slots are integral_constants so that every
+    // register array is indexed by constants only; tile t lives in slot (t - t_beg) % PF.
+    auto run_segment = [&](auto nq_c) {
+      constexpr int NQ = decltype(nq_c)::value;
+      constexpr std::false_type body{};
+      constexpr std::true_type tail{};
+      for (int attempt = 0; attempt < 2; ++attempt) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+          lacc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        if (attempt == 1) exact_max(nq_c);
+
+        page_ids(t_beg, idr0[0], idr1[0]);
+        if constexpr (PF > 1) page_ids(t_beg + 1, idr0[1], idr1[1]);
+        if constexpr (PF > 2) page_ids(t_beg + 2, idr0[2], idr1[2]);
+        if constexpr (PF > 3) page_ids(t_beg + 3, idr0[3], idr1[3]);
+        issue(std::integral_constant<int, 0>{}, t_beg);
+        if constexpr (PF > 1) issue(std::integral_constant<int, 1>{}, t_beg + 1);
+        if constexpr (PF > 2) issue(std::integral_constant<int, 2>{}, t_beg + 2);
+        if constexpr (PF > 3) issue(std::integral_constant<int, 3>{}, t_beg + 3);
+
+        if (attempt == 0) {
+          // reference max = max of the segment's first tile (already in ring slot 0)
+          const int tb = t_beg * kTile;
+#pragma unroll
+          for (int qb = 0; qb < NQ; ++qb) {
+            f32x4 s0, s1;
+            scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > first_query_pos, s0, s1);
+            m[qb] = quad_row_max(max8(s0, s1));
+            mcq[qb] = (m[qb] == -INFINITY ? 0.f : m[qb]) * c;    // nothing visible: any reference
+          }
+        }
+
+        int tile = t_beg;
+        while (tile + PF <= fast_stop) {                 // steady state: fully visible tiles
+          DIAG_STAMP();
+          tile_step(nq_c, body, std::integral_constant<int, 0>{}, tile);
+          issue(std::integral_constant<int, 0>{}, tile + PF);
+          if constexpr (PF > 1) {
+            tile_step(nq_c, body, std::integral_constant<int, 1>{}, tile + 1);
+            issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
+          }
+          if constexpr (PF > 2) {
+            tile_step(nq_c, body, std::integral_constant<int, 2>{}, tile + 2);
+            issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
+          }
+          if constexpr (PF > 3) {
+            tile_step(nq_c, body, std::integral_constant<int, 3>{}, tile + 3);
+            issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
+          }
+          tile += PF;
+        }
+        for (; tile < t_end; tile += PF) {               // causal tail, and what is left over
+          DIAG_STAMP();
+          tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
+          issue(std::integral_constant<int, 0>{}, tile + PF);
+          if constexpr (PF > 1) {
+            if (tile + 1 < t_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, tile + 1);
+            issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
+          }
+          if constexpr (PF > 2) {
+            if (tile + 2 < t_end) tile_step(nq_c, tail, std::integral_constant<int, 2>{}, tile + 2);
+            issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
+          }
+          if constexpr (PF > 3) {
+            if (tile + 3 < t_end) tile_step(nq_c, tail, std::integral_constant<int, 3>{}, tile + 3);
+            issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
+          }
+        }
+
+        // A reference far below the true max shows up as an overflowed (or NaN) denominator.
+        bool bad = false;
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) bad |= !(lacc[qb][0] < 1e37f);
+        if (__builtin_amdgcn_ballot_w64(bad) == 0) break;
+      }
+    };
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) { m[qb] = -INFINITY; mcq[qb] = 0.f; }
+    switch (nqb) {
+      case 1: run_segment(std::integral_constant<int, 1>{}); break;
+      case 2: if constexpr (NQB >= 2) run_segment(std::integral_constant<int, 2>{}); break;
+      case 3: if constexpr (NQB >= 3) run_segment(std::integral_constant<int, 3>{}); break;
+      default: if constexpr (NQB >= 4) run_segment(std::integral_constant<int, 4>{}); break;
     }
 
+    DIAG_STAMP();
     // ---- finish the segment ----
+    float l[NQB];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) l[qb] = quad_row_sum(l[qb]);
+    for (int qb = 0; qb < NQB; ++qb) l[qb] = lacc[qb][0];
     const bool complete = (t_beg == 0) && (t_end == tiles);
     if (complete) {
 #pragma unroll
@@ -462,8 +597,13 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
 template <int D>
 hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
                     const BatchDev& b, float c, void* ws, hipStream_t stream) {
-  constexpr int PF_SMALL = (D == 128) ? 3 : 4;   // up to 32 queries per tile
-  constexpr int PF_LARGE = (D == 128) ? 2 : 4;   // 48 or 64 queries per tile
+#ifndef MTS_PF_A
+#define MTS_PF_A 4   // D <= 64
+#define MTS_PF_B 3   // D = 128, up to 32 queries per tile
+#define MTS_PF_C 2   // D = 128, 48 or 64 queries per tile
+#endif
+  constexpr int PF_SMALL = (D == 128) ? MTS_PF_B : MTS_PF_A;   // up to 32 queries per tile
+  constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;   // 48 or 64 queries per tile
   switch (plan.q_tile / 16) {
     case 1: return launch_one<D, 1, PF_SMALL>(g, plan, q, out, b, c, ws, stream);
     case 2: return launch_one<D, 2, PF_SMALL>(g, plan, q, out, b, c, ws, stream);
