@@ -13,35 +13,30 @@
 //
 // Operand flow.  Scores are computed transposed, S^T = K Q^T with v_mfma_f32_16x16x32_bf16:
 // tokens are the M rows, queries the N columns, so a lane's accumulator values belong to ONE
-// query; softmax statistics are per-lane scalars and the tile max needs two cross-lane
-// swaps.  With the pool's K slot order, the 8 values a lane holds after the two half-tiles
-// are 8 consecutive tokens, which is exactly the B fragment of O^T = V^T P^T; V is stored
-// [dim][token], so its A fragment is one 16-byte load.  Nothing is staged through LDS: each
-// 16-byte global load is already an MFMA fragment, a wavefront's loads cover whole 512-byte
-// runs of a page, and a ring of PF tiles per wavefront is kept in flight in registers.
+// query and softmax statistics are per-lane scalars.  With the pool's K slot order, the 8
+// values a lane holds after the two half-tiles are 8 consecutive tokens, which is exactly the
+// B fragment of O^T = V^T P^T; V is stored [dim][token], so its A fragment is one 16-byte
+// load.  Nothing is staged through LDS: each 16-byte global load is already an MFMA fragment
+// and a wavefront's loads cover whole 512-byte runs of a page.
+//
+// Pipeline.  Each wavefront keeps a ring of PF tiles in flight in registers.  All loads of the
+// steady state are unconditional (positions past a segment's end repeat its last tile), so the
+// in-order vector-memory counter can be waited on exactly; page ids travel through scalar
+// loads, whose counter is separate.
+//
+// Softmax.  The reference max of a segment is fixed once, from its first tile, and never
+// moved: softmax is shift-invariant, and weights above 1 are as exact in bf16 / fp32 as
+// weights below 1, so the inner loop has no running max, no rescaling and no cross-lane step.
+// Row sums come from the matrix core (a ones fragment times P^T).  Should the first tile have
+// been so unrepresentative that a denominator overflows, the segment is redone with the exact
+// max, found by a K-only pass.
 #include <math.h>
 
 #include <type_traits>
 
 #include "mts_internal.hpp"
 
-#ifndef MTS_DIAG
-#define MTS_DIAG 0
-#endif
 
-#if MTS_DIAG == 6
-__device__ long long g_mts_diag[16 * 128];
-extern "C" int mts_diag_dump(long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_mts_diag), sizeof(g_mts_diag));
-}
-#define DIAG_STAMP()                                                                  \
-  do {                                                                                \
-    if ((wid & 63) == 0 && lane == 0 && diag_n < 128) g_mts_diag[(wid >> 6) * 128 + diag_n] = wall_clock64(); \
-    ++diag_n;                                                                         \
-  } while (0)
-#else
-#define DIAG_STAMP() do {} while (0)
-#endif
 
 namespace mts {
 namespace {
@@ -124,11 +119,6 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
   const int wave = uniform(tid >> 6);
   const int r = lane & 15, gq = lane >> 4;
   const int H = g.H, S = g.S;
-#if MTS_DIAG == 6
-  int diag_n = 0;
-  const int wid_early = blockIdx.x * kWavesPerWg + wave;
-  { const int wid = wid_early; DIAG_STAMP(); }
-#endif
 
   // ---- schedule: every workgroup computes the same prefix sum --------------------------
   {
@@ -168,7 +158,6 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
   int lo, hi;
   wave_share(total, num_waves, min_tiles, wid, &lo, &hi);
   if (lo >= hi) return;                                // no barrier below this line
-  DIAG_STAMP();
 
   const int sub_mask = (1 << g.sub_shift) - 1;
   const int64_t v_off = (int64_t)S * D * 2;            // K block -> V block of the same head
@@ -233,9 +222,6 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
       id1 = npg > 0 ? b.page_indices[pbeg + lp1] : 0;
     };
     auto tile_bases = [&](int tile, int id0, int id1, const char*& kb0, const char*& kb1) {
-#if MTS_DIAG == 1
-      tile = t_beg;                                    // diagnostic: every load hits the same tile
-#endif
       const int tl = tile < last_tile ? tile : last_tile;
       const int sb0 = tl * 2, sb1 = sb0 + 1;
       if ((unsigned)id0 >= (unsigned)g.num_pages) id0 = 0;
@@ -251,12 +237,6 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
     // exactly) into ring slot p, then requests the ids of the tile this slot loads next.
     auto issue = [&](auto buf, int tile) {            // buf is an integral_constant: register ring slot
       constexpr int p = decltype(buf)::value;
-#if MTS_DIAG == 4
-      if (tile >= t_beg + PF) return;                  // diagnostic: no loads after the prologue
-#endif
-#if MTS_DIAG == 5
-      if (tile >= t_beg + PF) { page_ids(tile + PF, idr0[p], idr1[p]); return; }   // only the id loads
-#endif
       const char *kb0, *kb1;
       tile_bases(tile, idr0[p], idr1[p], kb0, kb1);
       // K fragments: rows 0-7 of a half-tile come from sub-block 0, rows 8-15 from sub-block 1.
@@ -415,8 +395,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
 
         int tile = t_beg;
         while (tile + PF <= fast_stop) {                 // steady state: fully visible tiles
-          DIAG_STAMP();
-          tile_step(nq_c, body, std::integral_constant<int, 0>{}, tile);
+              tile_step(nq_c, body, std::integral_constant<int, 0>{}, tile);
           issue(std::integral_constant<int, 0>{}, tile + PF);
           if constexpr (PF > 1) {
             tile_step(nq_c, body, std::integral_constant<int, 1>{}, tile + 1);
@@ -433,8 +412,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
           tile += PF;
         }
         for (; tile < t_end; tile += PF) {               // causal tail, and what is left over
-          DIAG_STAMP();
-          tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
+              tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
           issue(std::integral_constant<int, 0>{}, tile + PF);
           if constexpr (PF > 1) {
             if (tile + 1 < t_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, tile + 1);
@@ -466,7 +444,6 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
       default: if constexpr (NQB >= 4) run_segment(std::integral_constant<int, 4>{}); break;
     }
 
-    DIAG_STAMP();
     // ---- finish the segment ----
     float l[NQB];
 #pragma unroll
