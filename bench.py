@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="batched_incremental")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy, as the known-size yardstick for HBM counters")
     return ap.parse_args()
 
 
@@ -50,9 +52,10 @@ def attention_flops_per_layer(w):
     return 4 * w.head_dim * w.heads * pairs
 
 
-def cpu_baseline(w, budget_s=20.0):
-    """The oracle, as it stands, on a bounded sample: whole users of the same workload, one
-    layer, all heads (unpack in host-chunk runs + append + attention + pack of one user)."""
+def cpu_baseline(w, budget_s=12.0):
+    """The oracle, as it stands, on a bounded sample of the same workload: whole users (all
+    heads), one layer's worth of work per pass - unpack of the history in host-chunk runs,
+    append, attention - repeated over fresh data until about `budget_s` seconds of CPU work."""
     import numpy as np
     import oracle
     import mts_workloads as W
@@ -62,10 +65,11 @@ def cpu_baseline(w, budget_s=20.0):
     except Exception:
         threads = 1
     rng = np.random.default_rng([w.seed, 99])
-    done_tokens, t_used, users = 0, 0.0, 0
-    for u in range(w.batch):
+    layer_tokens, t_used, passes = 0, 0.0, 0
+    while t_used < budget_s:
+        u = passes % w.batch
         P, n = int(w.prefix_lens[u]), int(w.new_lens[u])
-        sub = W.custom_workload("sample", w.seed + u, w.dtype, 1, w.heads, w.head_dim, w.page_size, [P], [n])
+        sub = W.custom_workload("sample", w.seed + passes, w.dtype, 1, w.heads, w.head_dim, w.page_size, [P], [n])
         hist = W.normal_elements(rng, (2, P, w.heads, w.head_dim), w.dtype)
         k = W.normal_elements(rng, (n, w.heads, w.head_dim), w.dtype)
         v = W.normal_elements(rng, (n, w.heads, w.head_dim), w.dtype)
@@ -77,15 +81,14 @@ def cpu_baseline(w, budget_s=20.0):
         oracle.append(store, 0, k, v, sub.page_indptr, sub.page_indices, sub.prefix_lens, sub.new_indptr)
         oracle.attn_incremental(store, 0, q, sub.page_indptr, sub.page_indices, sub.prefix_lens, sub.new_indptr)
         t_used += time.perf_counter() - t0
-        done_tokens += n
-        users += 1
-        if t_used > budget_s:
-            break
-    # one layer was timed; a step runs all layers over the same tokens
-    value = done_tokens / (t_used * w.layers)
+        layer_tokens += n
+        passes += 1
+    # a step runs all layers over the same new tokens: new tokens/s = (token x layer) rate / layers
+    value = layer_tokens / t_used / w.layers
     return {"value": value, "unit": "new_tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{users} of {w.batch} users (whole histories), 1 of {w.layers} layers timed and "
-                      f"scaled to {w.layers}; unpack+append+attention, fp64, {t_used:.1f} s of CPU work"}
+            "sample": f"{passes} (user, layer) passes over the workload's users in order, whole histories, all "
+                      f"heads: unpack + append + attention in fp64, {t_used:.1f} s of CPU work; rate divided by "
+                      f"the {w.layers} layers of a step"}
 
 
 def main():
@@ -192,6 +195,13 @@ def main():
     for s in range(K):
         step(attn_ev[s])
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.int32, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
 
     ms_per_step = (t1 - t0) * 1e3 / K
     attn_ms = [a.elapsed_time(b) for evs in attn_ev for (a, b) in evs]

@@ -129,7 +129,7 @@ AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   p.q_tiles_max = (max_new + p.q_tile - 1) / p.q_tile;
   const int64_t items = (int64_t)b.batch * p.q_tiles_max;
   const int64_t tiles_upper = items * ((b.max_total_len + 31) / 32) * g.H;   // kv tiles of the call
-  if (items > 16384 || tiles_upper >= (1ll << 31)) { p.too_large = true; return p; }
+  if (items > 16384 || b.batch > 4096 || tiles_upper >= (1ll << 31)) { p.too_large = true; return p; }
   p.n_items = (int)items;
   // a wavefront's share is never shorter than this: below it, start-up and the partial
   // accumulators cost more than the share itself
@@ -140,8 +140,8 @@ AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   if (const char* env = getenv("MTS_ATTN_MAX_WAVES")) { const int v = atoi(env); if (v >= 4) cap = v / 4 * 4; }
   p.max_waves = (int)(waves < cap ? waves : cap);
   if (p.max_waves < 4) p.max_waves = 4;
-  p.ws_cum_bytes = roundup((items + 1) * (int64_t)sizeof(int), 256);
-  p.ws_bytes = p.ws_cum_bytes + (int64_t)p.max_waves * 2 * p.q_tile * (g.D + 2) * (int64_t)sizeof(float);
+  p.ws_desc_bytes = roundup((int64_t)p.max_waves * 32, 256);
+  p.ws_bytes = p.ws_desc_bytes + (int64_t)p.max_waves * 2 * p.q_tile * (g.D + 2) * (int64_t)sizeof(float);
   return p;
 }
 
@@ -247,8 +247,8 @@ int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const v
   if (!aligned(q, 16) || !aligned(out, 16)) return fail(MTS_ERR_INVALID_ARG, "q / out is not 16-byte aligned");
   const mts::AttnPlan plan = mts::plan_attention(g, b);
   if (plan.too_large)
-    return fail(MTS_ERR_UNSUPPORTED, "batch %d x ceil(max_new %d / 64) exceeds 16384 query tiles, or the call "
-                "has 2^31 or more kv tiles", b.batch, b.max_new);
+    return fail(MTS_ERR_UNSUPPORTED, "batch %d exceeds 4096 users, batch x ceil(max_new %d / 64) exceeds 16384 "
+                "query tiles, or the call has 2^31 or more kv tiles", b.batch, b.max_new);
   if (plan.ws_bytes > 0) {
     if (!workspace) return fail(MTS_ERR_WORKSPACE, "workspace is NULL but %lld bytes are needed", (long long)plan.ws_bytes);
     if (workspace_bytes < plan.ws_bytes)

@@ -60,103 +60,105 @@ __device__ __forceinline__ float quad_row_max(float v) {
   auto b = __builtin_amdgcn_permlane16_swap(u, u, false, false);
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
-// ---- schedule, shared by the attention and the merge kernel -------------------------------
-struct Item {            // one (user, query tile)
-  int tok0, n_u, P, q0, q1, tiles;   // tiles = kv tiles visible to the tile's last query
-};
-
-__device__ __forceinline__ Item load_item(const BatchDev& b, int item, int q_tiles_max, int q_tile) {
-  Item it;
-  const int u = item / q_tiles_max, qt = item % q_tiles_max;
-  it.tok0 = b.new_indptr[u];
-  it.n_u = b.new_indptr[u + 1] - it.tok0;
-  it.P = b.prefix_lens[u];
-  it.q0 = qt * q_tile;
-  it.q1 = (it.n_u < it.q0 + q_tile) ? it.n_u : (it.q0 + q_tile);
-  it.tiles = (it.q0 < it.n_u) ? (it.P + it.q1 + kTile - 1) / kTile : 0;
-  return it;
-}
-
 // share of wavefront w: [lo, hi) in global tile positions
-__device__ __forceinline__ void wave_share(int total, int num_waves, int min_tiles, int w, int* lo, int* hi) {
-  int per = (total + num_waves - 1) / num_waves;
-  if (per < min_tiles) per = min_tiles;
-  const long long l = (long long)w * per;
-  *lo = l < total ? (int)l : total;
-  *hi = (l + per) < total ? (int)(l + per) : total;
-}
 __device__ __forceinline__ int tiles_per_wave(int total, int num_waves, int min_tiles) {
   const int per = (total + num_waves - 1) / num_waves;
   return per < min_tiles ? min_tiles : per;
 }
-
-// largest i in [0, n) with cum[i] <= pos   (cum is non-decreasing, cum[0] = 0, pos < cum[n])
-template <typename P>
-__device__ __forceinline__ int find_item(P cum, int n, int pos) {
-  int lo = 0, hi = n;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (cum[mid] <= pos) lo = mid; else hi = mid;
-  }
-  return lo;
+__device__ __forceinline__ void wave_share(int total, int num_waves, int min_tiles, int w, int* lo, int* hi) {
+  const int per = tiles_per_wave(total, num_waves, min_tiles);
+  const long long l = (long long)w * per;
+  *lo = l < total ? (int)l : total;
+  *hi = (l + per) < total ? (int)(l + per) : total;
 }
+
+// What the merge kernel needs to finish one (query tile, head) cut by share boundaries;
+// written by the wavefront that holds the pair's first tile.
+struct MergeDesc {
+  int valid;       // 1: this wavefront starts a cut pair
+  int w_last;      // last wavefront that holds a piece of it
+  int out_row;     // (token row of the tile's first query) * H + head
+  int nq;          // queries in the tile
+  int first_slot;  // partial slot of this wavefront's piece (0 leading, 1 trailing)
+  int pad[3];
+};
 
 template <int D, int NQB, int PF>
 __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b,
                                                           const uint16_t* __restrict__ q,
                                                           uint16_t* __restrict__ out, float c,
                                                           int q_tiles_max, int n_items, int min_tiles,
-                                                          int* __restrict__ ws_cum,
+                                                          MergeDesc* __restrict__ ws_desc,
                                                           float* __restrict__ ws_o,
                                                           float* __restrict__ ws_ml) {
   constexpr int QT = 16 * NQB;       // queries per query tile
   constexpr int KS = D / 32;         // k-steps of Q.K
   constexpr int DB = D / 16;         // 16-dim blocks of the output
 
-  extern __shared__ int lds_cum[];   // [n_items + 1] exclusive prefix of tiles * H, then 4 wave totals
+  // LDS: per-user metadata and the schedule's prefix sums
+  extern __shared__ int lds[];
+  const int B = b.batch;
+  int* s_tok = lds;                  // [B+1] new_indptr
+  int* s_pg = s_tok + (B + 1);       // [B+1] page_indptr
+  int* s_P = s_pg + (B + 1);         // [B]   prefix_lens
+  int* s_cum = s_P + B;              // [n_items+1] exclusive prefix of tiles * H
+  int* s_wtot = s_cum + (n_items + 1);   // [4] wavefront totals of the scan
+
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
   const int r = lane & 15, gq = lane >> 4;
   const int H = g.H, S = g.S;
 
+  for (int k = tid; k <= B; k += 256) {
+    s_tok[k] = b.new_indptr[k];
+    s_pg[k] = b.page_indptr[k];
+    if (k < B) s_P[k] = b.prefix_lens[k];
+  }
+  __syncthreads();
+
+  // kv tiles visible to the last query of (user, query tile) `item`; 0 if the tile is empty
+  auto item_tiles = [&](int item) -> int {
+    const int u = item / q_tiles_max, q0 = (item % q_tiles_max) * QT;
+    const int n_u = s_tok[u + 1] - s_tok[u];
+    if (q0 >= n_u) return 0;
+    const int q1 = (n_u < q0 + QT) ? n_u : (q0 + QT);
+    return (s_P[u] + q1 + kTile - 1) / kTile;
+  };
+
   // ---- schedule: every workgroup computes the same prefix sum --------------------------
   {
     const int per_thread = (n_items + 255) / 256;
     const int first = tid * per_thread;
     int local = 0;
-    for (int k = 0; k < per_thread; ++k) {
-      const int item = first + k;
-      if (item < n_items) local += load_item(b, item, q_tiles_max, QT).tiles * H;
-    }
+    for (int k = 0; k < per_thread; ++k)
+      if (first + k < n_items) local += item_tiles(first + k) * H;
     int incl = local;                                  // inclusive scan over the wavefront
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int up = __shfl_up(incl, o);
       if (lane >= o) incl += up;
     }
-    int* wave_tot = lds_cum + n_items + 1;
-    if (lane == 63) wave_tot[wave] = incl;
+    if (lane == 63) s_wtot[wave] = incl;
     __syncthreads();
     int base = incl - local;
-    for (int w = 0; w < wave; ++w) base += wave_tot[w];
+    for (int w = 0; w < wave; ++w) base += s_wtot[w];
     for (int k = 0; k < per_thread; ++k) {
-      const int item = first + k;
-      if (item < n_items) {
-        lds_cum[item] = base;
-        base += load_item(b, item, q_tiles_max, QT).tiles * H;
+      if (first + k < n_items) {
+        s_cum[first + k] = base;
+        base += item_tiles(first + k) * H;
       }
     }
-    if (tid == 255) lds_cum[n_items] = base;
+    if (tid == 255) s_cum[n_items] = base;
     __syncthreads();
-    if (blockIdx.x == 0)                               // the merge kernel reads it from here
-      for (int k = tid; k <= n_items; k += 256) ws_cum[k] = lds_cum[k];
   }
-  const int total = lds_cum[n_items];
+  const int total = s_cum[n_items];
   const int num_waves = gridDim.x * kWavesPerWg;
   const int wid = blockIdx.x * kWavesPerWg + wave;
+  const int per_wave = tiles_per_wave(total, num_waves, min_tiles);
   int lo, hi;
   wave_share(total, num_waves, min_tiles, wid, &lo, &hi);
+  if (lane == 0) ws_desc[wid].valid = 0;
   if (lo >= hi) return;                                // no barrier below this line
 
   const int sub_mask = (1 << g.sub_shift) - 1;
@@ -166,25 +168,36 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
   int pos = lo;
-  int item = find_item(lds_cum, n_items, pos);
+  int item = 0;
+  {
+    int a = 0, e = n_items;                            // largest i with s_cum[i] <= lo
+    while (e - a > 1) {
+      const int mid = (a + e) >> 1;
+      if (s_cum[mid] <= lo) a = mid; else e = mid;
+    }
+    item = a;
+  }
   while (pos < hi) {
-    while (lds_cum[item + 1] <= pos) ++item;           // skips (user, query tile)s without work
+    while (s_cum[item + 1] <= pos) ++item;             // skips (user, query tile)s without work
     const int u = item / q_tiles_max;
-    const Item it = load_item(b, item, q_tiles_max, QT);
-    const int tiles = uniform(it.tiles);
-    const int item_pos = lds_cum[item];
-    const int h = uniform((pos - item_pos) / tiles);
-    const int t_beg = uniform((pos - item_pos) % tiles);
+    const int tok0 = uniform(s_tok[u]);
+    const int n_u = uniform(s_tok[u + 1]) - tok0;
+    const int P = uniform(s_P[u]);
+    const int q0 = (item % q_tiles_max) * QT;
+    const int q1 = (n_u < q0 + QT) ? n_u : (q0 + QT);
+    const int nq = q1 - q0;
+    const int tiles = (P + q1 + kTile - 1) / kTile;    // kv tiles of the whole (query tile, head)
+    const int item_pos = uniform(s_cum[item]);
+    const int h = (pos - item_pos) / tiles;
+    const int t_beg = (pos - item_pos) % tiles;
     const int pair_end = item_pos + (h + 1) * tiles;
     const int seg_end = pair_end < hi ? pair_end : hi;
-    const int t_end = uniform(t_beg + (seg_end - pos));
-    const int tok0 = uniform(it.tok0), n_u = uniform(it.n_u), P = uniform(it.P);
-    const int q0 = uniform(it.q0), nq = uniform(it.q1 - it.q0);
+    const int t_end = t_beg + (seg_end - pos);
     const int nqb = (nq + 15) >> 4;
     const int T_u = P + n_u;                           // tokens that hold data
     const int first_query_pos = P + q0;
-    const int pbeg = uniform(b.page_indptr[u]);
-    const int npg = uniform(b.page_indptr[u + 1]) - pbeg;
+    const int pbeg = uniform(s_pg[u]);
+    const int npg = uniform(s_pg[u + 1]) - pbeg;
     const char* head_base = g.layer_base + (int64_t)h * 2 * S * D * 2;
 
     // Q^T fragments: lane (r, gq) holds query q0+16*qb+r, dims 32*s + 8*gq .. +7.
@@ -449,13 +462,14 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) l[qb] = lacc[qb][0];
     const bool complete = (t_beg == 0) && (t_end == tiles);
+    const int out_row = (tok0 + q0) * H + h;           // row of query 0, in [token * H + head] units
     if (complete) {
 #pragma unroll
       for (int qb = 0; qb < NQB; ++qb) {
         const int qi = 16 * qb + r;
         if (qi < nq) {
           const float inv = 1.0f / l[qb];
-          uint16_t* orow = out + ((int64_t)(tok0 + q0 + qi) * H + h) * D + 4 * gq;
+          uint16_t* orow = out + ((int64_t)out_row + (int64_t)qi * H) * D + 4 * gq;
 #pragma unroll
           for (int db = 0; db < DB; ++db) {
             bf16x4 ob;
@@ -481,50 +495,48 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b
           }
         }
       }
+      if (t_beg == 0 && lane == 0) {
+        // this share holds the pair's first tile: it owns the merge of all the pieces
+        MergeDesc d;
+        d.valid = 1;
+        d.w_last = (pair_end - 1) / per_wave;
+        d.out_row = out_row;
+        d.nq = nq;
+        d.first_slot = slot;
+        d.pad[0] = d.pad[1] = d.pad[2] = 0;
+        ws_desc[wid] = d;
+      }
     }
     pos = seg_end;
   }
 }
 
-// Finishes the (query tile, head)s that a share boundary cut: workgroup w looks at the pair
-// that holds the last tile of share w; if that pair starts inside share w and continues past
-// it, w merges the partials of all shares that touch it, in share order.
+// Finishes the (query tile, head)s that a share boundary cut.  Workgroup w serves the pair
+// whose first tile lies in share w (if that pair continues into later shares): a numerically
+// safe weighted sum of the pieces, in share order.  Share w holds its piece in slot
+// `first_slot`; every later share holds its piece as the leading one (slot 0).
 template <int D>
-__global__ __launch_bounds__(256) void attn_merge_kernel(BatchDev b, int H, uint16_t* __restrict__ out,
-                                                         float c, int q_tile, int q_tiles_max, int n_items,
-                                                         int min_tiles, int num_waves,
-                                                         const int* __restrict__ ws_cum,
+__global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ out, float c, int q_tile,
+                                                         int H, const MergeDesc* __restrict__ ws_desc,
                                                          const float* __restrict__ ws_o,
                                                          const float* __restrict__ ws_ml) {
   const int w = blockIdx.x;
-  const int total = ws_cum[n_items];
-  int lo, hi;
-  wave_share(total, num_waves, min_tiles, w, &lo, &hi);
-  if (lo >= hi) return;
-  const int item = find_item(ws_cum, n_items, hi - 1);
-  const Item it = load_item(b, item, q_tiles_max, q_tile);
-  const int item_pos = ws_cum[item];
-  const int h = (hi - 1 - item_pos) / it.tiles;
-  const int pair_beg = item_pos + h * it.tiles;
-  const int pair_end = pair_beg + it.tiles;
-  if (!(pair_end > hi && pair_beg >= lo)) return;      // not cut, or another share owns the merge
-  const int per = tiles_per_wave(total, num_waves, min_tiles);
-  const int w_last = (pair_end - 1) / per;
-  const int nq = it.q1 - it.q0;
+  const MergeDesc d = ws_desc[w];
+  if (!d.valid) return;
   constexpr int D4 = D / 4;
-  for (int e = threadIdx.x; e < nq * D4; e += blockDim.x) {
+  for (int e = threadIdx.x; e < d.nq * D4; e += blockDim.x) {
     const int qi = e / D4, d4 = e % D4;
     float M = -INFINITY;
-    for (int ww = w; ww <= w_last; ++ww) {
-      const int slot = ((long long)ww * per >= pair_beg) ? 0 : 1;
+    for (int ww = w; ww <= d.w_last; ++ww) {
+      const int slot = (ww == w) ? d.first_slot : 0;
       M = fmaxf(M, ws_ml[(((int64_t)ww * 2 + slot) * q_tile + qi) * 2]);
     }
     f32x4 num = {0.f, 0.f, 0.f, 0.f};
     float den = 0.f;
-    for (int ww = w; ww <= w_last; ++ww) {
-      const int slot = ((long long)ww * per >= pair_beg) ? 0 : 1;
+    for (int ww = w; ww <= d.w_last; ++ww) {
+      const int slot = (ww == w) ? d.first_slot : 0;
       const int64_t prow = ((int64_t)ww * 2 + slot) * q_tile + qi;
-      const float wgt = fast_exp2((ws_ml[prow * 2] - M) * c);   // a share that saw no visible key has max -inf
+      const float wgt = fast_exp2((ws_ml[prow * 2] - M) * c);   // a piece with no visible key has max -inf
       const f32x4 part = *reinterpret_cast<const f32x4*>(ws_o + prow * D + 4 * d4);
       num += part * wgt;
       den = fmaf(wgt, ws_ml[prow * 2 + 1], den);
@@ -533,7 +545,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(BatchDev b, int H, uint
     bf16x4 ob;
 #pragma unroll
     for (int k = 0; k < 4; ++k) ob[k] = (__bf16)(num[k] * inv);
-    *reinterpret_cast<bf16x4*>(out + ((int64_t)(it.tok0 + it.q0 + qi) * H + h) * D + 4 * d4) = ob;
+    *reinterpret_cast<bf16x4*>(out + ((int64_t)d.out_row + (int64_t)qi * H) * D + 4 * d4) = ob;
   }
 }
 
@@ -541,8 +553,9 @@ template <int D, int NQB, int PF>
 hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
                       const BatchDev& b, float c, void* workspace, hipStream_t stream) {
   auto kern = attn_stream_kernel<D, NQB, PF>;
-  const size_t lds_bytes = sizeof(int) * (plan.n_items + 1 + kWavesPerWg);
+  const size_t lds_bytes = sizeof(int) * ((size_t)3 * b.batch + 2 + plan.n_items + 1 + kWavesPerWg);
   static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
+  static size_t lds_limit = 48 * 1024;
   if (wgs_per_cu == 0) {
     int dev = 0, n = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -552,20 +565,25 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
     num_cus = cus > 0 ? cus : 256;
     wgs_per_cu = n < 1 ? 1 : (n > 2 ? 2 : n);
   }
+  if (lds_bytes > lds_limit) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    lds_limit = lds_bytes;
+  }
   int wgs = num_cus * wgs_per_cu;
   if (wgs * kWavesPerWg > plan.max_waves) wgs = plan.max_waves / kWavesPerWg;
   if (wgs < 1) wgs = 1;
   char* ws = static_cast<char*>(workspace);
-  int* ws_cum = reinterpret_cast<int*>(ws);
-  float* ws_o = reinterpret_cast<float*>(ws + plan.ws_cum_bytes);
+  MergeDesc* ws_desc = reinterpret_cast<MergeDesc*>(ws);
+  float* ws_o = reinterpret_cast<float*>(ws + plan.ws_desc_bytes);
   float* ws_ml = ws_o + (int64_t)plan.max_waves * 2 * plan.q_tile * g.D;
   hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, out, c, plan.q_tiles_max,
-                     plan.n_items, plan.min_tiles, ws_cum, ws_o, ws_ml);
+                     plan.n_items, plan.min_tiles, ws_desc, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(wgs * kWavesPerWg), dim3(256), 0, stream, b, g.H, out, c,
-                     plan.q_tile, plan.q_tiles_max, plan.n_items, plan.min_tiles, wgs * kWavesPerWg,
-                     ws_cum, ws_o, ws_ml);
+  hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(wgs * kWavesPerWg), dim3(256), 0, stream, out, c,
+                     plan.q_tile, g.H, ws_desc, ws_o, ws_ml);
   return hipGetLastError();
 }
 
@@ -579,8 +597,8 @@ hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, 
 #define MTS_PF_B 3   // D = 128, up to 32 queries per tile
 #define MTS_PF_C 2   // D = 128, 48 or 64 queries per tile
 #endif
-  constexpr int PF_SMALL = (D == 128) ? MTS_PF_B : MTS_PF_A;   // up to 32 queries per tile
-  constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;   // 48 or 64 queries per tile
+  constexpr int PF_SMALL = (D == 128) ? MTS_PF_B : MTS_PF_A;
+  constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;
   switch (plan.q_tile / 16) {
     case 1: return launch_one<D, 1, PF_SMALL>(g, plan, q, out, b, c, ws, stream);
     case 2: return launch_one<D, 2, PF_SMALL>(g, plan, q, out, b, c, ws, stream);

@@ -44,7 +44,7 @@ struct AttnPlan {
   int32_t n_items;       // batch * q_tiles_max
   int32_t min_tiles;     // least kv tiles a wavefront's share may hold
   int32_t max_waves;     // most wavefronts the launch may use (sizes the partial buffers)
-  int64_t ws_cum_bytes;  // schedule prefix sums at the start of the workspace
+  int64_t ws_desc_bytes; // per-wavefront merge descriptors at the start of the workspace
   int64_t ws_bytes;      // whole workspace
 };
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b);
