@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 256 MiB device copy, as the known-size yardstick for HBM counters")
+                    help="also run one plain 1 GiB device copy, as the known-size yardstick for HBM counters")
     return ap.parse_args()
 
 
@@ -113,6 +113,8 @@ def main():
     L, H, D = w.layers, w.heads, w.head_dim
     torch.manual_seed(w.seed)
 
+    if args.calibrate_copy:
+        cal_src = torch.empty(256 << 20, dtype=torch.int32, device=dev).fill_(7)
     # ---- inputs, resident in HBM before timing ------------------------------------------
     cache = PagedKVCache(L, w.num_pages, w.page_size, H, D, w.dtype, dev)
     cache.pool.view(torch.bfloat16).normal_()            # every slot ~ N(0,1): K/V of all users
@@ -197,10 +199,10 @@ def main():
     torch.cuda.synchronize()
 
     if args.calibrate_copy:
-        src = torch.empty(64 << 20, dtype=torch.int32, device=dev).fill_(7)
-        dst = torch.empty_like(src)
+        # cal_src was filled before all the work above, so none of it is left in any cache
+        cal_dst = torch.empty_like(cal_src)
         torch.cuda.synchronize()
-        dst.copy_(src)                                   # reads 256 MiB, writes 256 MiB
+        cal_dst.copy_(cal_src)                           # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
 
     ms_per_step = (t1 - t0) * 1e3 / K
