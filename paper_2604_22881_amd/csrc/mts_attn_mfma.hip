@@ -83,8 +83,9 @@ struct MergeDesc {
   int pad[3];
 };
 
-template <int D, int NQB, int PF>
-__global__ __launch_bounds__(256) void attn_stream_kernel(PoolGeom g, BatchDev b,
+// WPS = wavefronts per SIMD the kernel is compiled for (bounds its registers)
+template <int D, int NQB, int PF, int WPS>
+__global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, BatchDev b,
                                                           const uint16_t* __restrict__ q,
                                                           uint16_t* __restrict__ out, float c,
                                                           int q_tiles_max, int n_items, int min_tiles,
@@ -520,39 +521,57 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ 
                                                          int H, const MergeDesc* __restrict__ ws_desc,
                                                          const float* __restrict__ ws_o,
                                                          const float* __restrict__ ws_ml) {
+  // One thread per (query, 4 dims); pieces are taken four at a time with all their loads issued
+  // together, and folded into a running (max, numerator, denominator) - in share order.
   const int w = blockIdx.x;
   const MergeDesc d = ws_desc[w];
-  if (!d.valid) return;
   constexpr int D4 = D / 4;
-  for (int e = threadIdx.x; e < d.nq * D4; e += blockDim.x) {
-    const int qi = e / D4, d4 = e % D4;
-    float M = -INFINITY;
-    for (int ww = w; ww <= d.w_last; ++ww) {
-      const int slot = (ww == w) ? d.first_slot : 0;
-      M = fmaxf(M, ws_ml[(((int64_t)ww * 2 + slot) * q_tile + qi) * 2]);
-    }
-    f32x4 num = {0.f, 0.f, 0.f, 0.f};
-    float den = 0.f;
-    for (int ww = w; ww <= d.w_last; ++ww) {
+  const int e = blockIdx.y * 256 + threadIdx.x;
+  if (!d.valid || e >= d.nq * D4) return;
+  const int qi = e / D4, d4 = e % D4;
+  float M = -INFINITY, den = 0.f;
+  f32x4 num = {0.f, 0.f, 0.f, 0.f};
+  for (int w0 = w; w0 <= d.w_last; w0 += 4) {
+    float pm[4], pl[4];
+    f32x4 po[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int ww = (w0 + k <= d.w_last) ? (w0 + k) : d.w_last;      // past the end: repeat, weight 0
       const int slot = (ww == w) ? d.first_slot : 0;
       const int64_t prow = ((int64_t)ww * 2 + slot) * q_tile + qi;
-      const float wgt = fast_exp2((ws_ml[prow * 2] - M) * c);   // a piece with no visible key has max -inf
-      const f32x4 part = *reinterpret_cast<const f32x4*>(ws_o + prow * D + 4 * d4);
-      num += part * wgt;
-      den = fmaf(wgt, ws_ml[prow * 2 + 1], den);
+      pm[k] = ws_ml[prow * 2];
+      pl[k] = ws_ml[prow * 2 + 1];
+      po[k] = *reinterpret_cast<const f32x4*>(ws_o + prow * D + 4 * d4);
     }
-    const float inv = 1.0f / den;
-    bf16x4 ob;
+    float Mn = M;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) ob[k] = (__bf16)(num[k] * inv);
-    *reinterpret_cast<bf16x4*>(out + ((int64_t)d.out_row + (int64_t)qi * H) * D + 4 * d4) = ob;
+    for (int k = 0; k < 4; ++k)
+      if (w0 + k <= d.w_last) Mn = fmaxf(Mn, pm[k]);
+    const float mref = (Mn == -INFINITY) ? 0.f : Mn;
+    const float rescale = fast_exp2((M - mref) * c);                   // 0 while nothing was folded in
+    num *= rescale;
+    den *= rescale;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (w0 + k <= d.w_last) {
+        const float wgt = fast_exp2((pm[k] - mref) * c);               // a piece with no visible key has max -inf
+        num += po[k] * wgt;
+        den = fmaf(wgt, pl[k], den);
+      }
+    }
+    M = Mn;
   }
+  const float inv = 1.0f / den;
+  bf16x4 ob;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) ob[k] = (__bf16)(num[k] * inv);
+  *reinterpret_cast<bf16x4*>(out + ((int64_t)d.out_row + (int64_t)qi * H) * D + 4 * d4) = ob;
 }
 
-template <int D, int NQB, int PF>
+template <int D, int NQB, int PF, int WPS>
 hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
                       const BatchDev& b, float c, void* workspace, hipStream_t stream) {
-  auto kern = attn_stream_kernel<D, NQB, PF>;
+  auto kern = attn_stream_kernel<D, NQB, PF, WPS>;
   const size_t lds_bytes = sizeof(int) * ((size_t)3 * b.batch + 2 + plan.n_items + 1 + kWavesPerWg);
   static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
   static size_t lds_limit = 48 * 1024;
@@ -582,28 +601,32 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
                      plan.n_items, plan.min_tiles, ws_desc, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(wgs * kWavesPerWg), dim3(256), 0, stream, out, c,
-                     plan.q_tile, g.H, ws_desc, ws_o, ws_ml);
+  hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(wgs * kWavesPerWg, (plan.q_tile * (D / 4) + 255) / 256), dim3(256), 0,
+                     stream, out, c, plan.q_tile, g.H, ws_desc, ws_o, ws_ml);
   return hipGetLastError();
 }
 
-// PF (tiles in flight per wavefront) is bounded by the register file: the ring holds
-// PF * D / 2 registers per lane beside the Q fragments and the output accumulators.
+// Launch shapes.  D <= 64: two wavefronts per SIMD with two tiles each in flight - the second
+// wavefront covers the first one's segment start-up and overlaps its VALU work with MFMA work.
+// D = 128: the accumulators and a useful ring need more than half the register file, so one
+// wavefront per SIMD with a deeper ring (3 tiles up to 32 queries per tile, else 2).
 template <int D>
 hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
                     const BatchDev& b, float c, void* ws, hipStream_t stream) {
 #ifndef MTS_PF_A
-#define MTS_PF_A 4   // D <= 64
+#define MTS_PF_A 2   // D <= 64
 #define MTS_PF_B 3   // D = 128, up to 32 queries per tile
 #define MTS_PF_C 2   // D = 128, 48 or 64 queries per tile
+#define MTS_WPS_A 2  // D <= 64
 #endif
   constexpr int PF_SMALL = (D == 128) ? MTS_PF_B : MTS_PF_A;
   constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;
+  constexpr int WPS = (D == 128) ? 1 : MTS_WPS_A;
   switch (plan.q_tile / 16) {
-    case 1: return launch_one<D, 1, PF_SMALL>(g, plan, q, out, b, c, ws, stream);
-    case 2: return launch_one<D, 2, PF_SMALL>(g, plan, q, out, b, c, ws, stream);
-    case 3: return launch_one<D, 3, PF_LARGE>(g, plan, q, out, b, c, ws, stream);
-    default: return launch_one<D, 4, PF_LARGE>(g, plan, q, out, b, c, ws, stream);
+    case 1: return launch_one<D, 1, PF_SMALL, WPS>(g, plan, q, out, b, c, ws, stream);
+    case 2: return launch_one<D, 2, PF_SMALL, WPS>(g, plan, q, out, b, c, ws, stream);
+    case 3: return launch_one<D, 3, PF_LARGE, WPS>(g, plan, q, out, b, c, ws, stream);
+    default: return launch_one<D, 4, PF_LARGE, WPS>(g, plan, q, out, b, c, ws, stream);
   }
 }
 

@@ -33,25 +33,35 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
   const int HC = H * dch;
   const int s = blockIdx.y;
 
-  // Resolve the run: user, first pool token, length, and the contiguous K / V planes.
+  // Resolve the run: user, first pool token, length, and the contiguous K / V planes.  The
+  // loads are ordered so that as few of them as possible wait for one another: nothing below
+  // returns early between two loads that do not depend on each other.
   int u, pos;
-  int64_t n;
+  int64_t n, t0;
+  if (MODE == MODE_APPEND) {
+    u = s;
+    t0 = b.new_indptr[u];
+    n = (int64_t)b.new_indptr[u + 1] - t0;
+    pos = b.prefix_lens[u];
+  } else {
+    u = segs.seg_user[s];
+    pos = segs.seg_pos[s];
+    t0 = segs.seg_tok_indptr[s];
+    n = segs.seg_tok_indptr[s + 1] - t0;
+  }
+  const bool user_ok = (u >= 0 && u < b.batch);
+  const int uc = user_ok ? u : 0;
+  const int pbeg = b.page_indptr[uc];
+  const int npg = b.page_indptr[uc + 1] - pbeg;
+
   const T* k_plane;
   const T* v_plane;
   T* k_out = nullptr;
   T* v_out = nullptr;
   if (MODE == MODE_APPEND) {
-    u = s;
-    const int64_t t0 = b.new_indptr[u];
-    n = (int64_t)b.new_indptr[u + 1] - t0;
-    pos = b.prefix_lens[u];
     k_plane = src_a + t0 * H * D;
     v_plane = src_b + t0 * H * D;
   } else {
-    u = segs.seg_user[s];
-    pos = segs.seg_pos[s];
-    const int64_t t0 = segs.seg_tok_indptr[s];
-    n = segs.seg_tok_indptr[s + 1] - t0;
     const int64_t base = t0 * 2 * H * D;
     k_plane = src_a + base;
     v_plane = k_plane + n * H * D;
@@ -60,23 +70,42 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
       v_out = k_out + n * H * D;
     }
   }
-  if (n <= 0 || pos < 0 || u < 0 || u >= b.batch) return;
-
-  const int64_t grp0 = pos / G;
-  const int64_t grp1 = (pos + n - 1) / G;
+  const bool run_ok = user_ok && n > 0 && pos >= 0;
+  const int64_t npos = run_ok ? n : 1, ppos = run_ok ? pos : 0;
+  const int64_t grp0 = ppos / G;
+  const int64_t grp1 = (ppos + npos - 1) / G;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (grp1 - grp0 + 1) * HC) return;
-  const int64_t grp = grp0 + idx / HC;
-  const int hc = (int)(idx % HC);
+  const bool mine = run_ok && idx < (grp1 - grp0 + 1) * HC;
+  const int64_t grp = grp0 + (mine ? idx / HC : 0);
+  const int hc = mine ? (int)(idx % HC) : 0;
   const int h = hc / dch, c = hc % dch;
   const int64_t tbase = grp * G;                       // first token of the aligned group
+  int lo = (int)((ppos > tbase ? ppos : tbase) - tbase);                          // valid tokens of
+  int hi = (int)(((ppos + npos) < (tbase + G) ? (ppos + npos) : (tbase + G)) - tbase);   // the group: [lo, hi)
+  if (!mine) lo = hi = 0;
+  const int64_t row0 = tbase - ppos;                   // contiguous-side row of group token 0
+  const int64_t col = (int64_t)h * D + c * G;
+
+  // contiguous-side loads first (unpack / append): they need nothing from the page table
+  Granule<T> krow[G], vrow[G];
+  if (MODE != MODE_PACK) {
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+      if (i >= lo && i < hi) {
+        const int64_t off = (row0 + i) * H * D + col;
+        krow[i].v = *reinterpret_cast<const uint4*>(k_plane + off);
+        vrow[i].v = *reinterpret_cast<const uint4*>(v_plane + off);
+      } else {
+        krow[i].v = make_uint4(0, 0, 0, 0);
+        vrow[i].v = make_uint4(0, 0, 0, 0);
+      }
+    }
+  }
 
   // One aligned group never straddles a 16-token sub-block, hence never a page.
-  const int pbeg = b.page_indptr[u];
-  const int npg = b.page_indptr[u + 1] - pbeg;
   const int64_t lp = tbase / S;
-  if (lp >= npg) return;
-  const int page = b.page_indices[pbeg + lp];
+  const bool page_ok = mine && lp < npg;
+  const int page = page_ok ? b.page_indices[pbeg + lp] : -1;
   if ((unsigned)page >= (unsigned)g.num_pages) return;
   const int slot = (int)(tbase % S);
   const int sub = slot >> 4, t16 = slot & 15;
@@ -84,24 +113,11 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
   T* kblk = reinterpret_cast<T*>(head + head_block_offset(0, h, S, D, sizeof(T))) + (int64_t)sub * 16 * D;
   T* vblk = reinterpret_cast<T*>(head + head_block_offset(1, h, S, D, sizeof(T))) + (int64_t)sub * 16 * D;
 
-  const int lo = (int)((pos > tbase ? pos : tbase) - tbase);                 // valid tokens of
-  const int hi = (int)(((pos + n) < (tbase + G) ? (pos + n) : (tbase + G)) - tbase);  // the group: [lo, hi)
-  const int64_t row0 = tbase - pos;                    // contiguous-side row of group token 0
-  const int64_t col = (int64_t)h * D + c * G;
-
   if (MODE != MODE_PACK) {
-    Granule<T> vrow[G];
 #pragma unroll
-    for (int i = 0; i < G; ++i) {
-      if (i >= lo && i < hi) {
-        const int64_t off = (row0 + i) * H * D + col;
-        const uint4 kg = *reinterpret_cast<const uint4*>(k_plane + off);
-        vrow[i].v = *reinterpret_cast<const uint4*>(v_plane + off);
-        *reinterpret_cast<uint4*>(kblk + k_sub_index(t16 + i, c * G, D, G)) = kg;
-      } else {
-        vrow[i].v = make_uint4(0, 0, 0, 0);
-      }
-    }
+    for (int i = 0; i < G; ++i)
+      if (i >= lo && i < hi)
+        *reinterpret_cast<uint4*>(kblk + k_sub_index(t16 + i, c * G, D, G)) = krow[i].v;
     if (lo == 0 && hi == G) {
 #pragma unroll
       for (int dd = 0; dd < G; ++dd) {
@@ -124,11 +140,13 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
     for (int dd = 0; dd < G; ++dd)
       vcol[dd].v = *reinterpret_cast<const uint4*>(vblk + v_sub_index(t16, c * G + dd));
 #pragma unroll
+    for (int i = 0; i < G; ++i)
+      krow[i].v = *reinterpret_cast<const uint4*>(kblk + k_sub_index(t16 + i, c * G, D, G));
+#pragma unroll
     for (int i = 0; i < G; ++i) {
       if (i >= lo && i < hi) {
         const int64_t off = (row0 + i) * H * D + col;
-        *reinterpret_cast<uint4*>(k_out + off) =
-            *reinterpret_cast<const uint4*>(kblk + k_sub_index(t16 + i, c * G, D, G));
+        *reinterpret_cast<uint4*>(k_out + off) = krow[i].v;
         Granule<T> o;
 #pragma unroll
         for (int dd = 0; dd < G; ++dd) o.e[dd] = vcol[dd].e[i];
