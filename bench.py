@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="batched_incremental")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
+    ap.add_argument("--no-miss", action="store_true", help="diagnostic: no restored users (no unpack, no per-layer wait)")
+    ap.add_argument("--no-evict", action="store_true", help="diagnostic: no packed users")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, as the known-size yardstick for HBM counters")
     return ap.parse_args()
@@ -127,11 +129,11 @@ def main():
     ws_bytes = mts.mts_attn_workspace_bytes(cache.desc, batch.meta)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
-    miss = [int(u) for u in w.miss_users if w.prefix_lens[u] > 0]
+    miss = [] if args.no_miss else [int(u) for u in w.miss_users if w.prefix_lens[u] > 0]
     miss_segs = SegmentList.for_histories(miss, [w.prefix_lens[u] for u in miss], w.chunk_tokens, dev)
     staging = [torch.randn(max(miss_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
                for _ in range(L)]                        # onload buffer contents, one per layer
-    evict = [int(u) for u in w.evict_users]
+    evict = [] if args.no_evict else [int(u) for u in w.evict_users]
     evict_segs = SegmentList.for_histories(evict, [w.total_lens[u] for u in evict], w.chunk_tokens, dev)
     offload = torch.empty(max(evict_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
 
@@ -232,6 +234,13 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "bytes_per_launch": alg_bytes, "avg_launch_ms": attn_ms_avg},
     }
+    if int(w.prefix_lens.sum()) == 0:
+        # cache-miss full prefill: a dense causal contraction, priced against the bf16 MFMA peak
+        # (flops = visible query-key pairs only; the masked half of the square is not counted)
+        tf = flops / (attn_ms_avg * 1e-3) / 1e12
+        res["roofline"].update({"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
+                                "flops_per_launch": flops})
     traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
     if os.path.exists(traffic_file):          # measured HBM bytes per launch, from rocprofv3 --pmc runs
         with open(traffic_file) as f:

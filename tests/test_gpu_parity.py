@@ -191,3 +191,33 @@ def test_empty_batch_and_no_new_tokens_are_noops():
     assert mts.mts_attn_incremental(cache.desc, 0, None, None, idle.meta) == 0
     torch.cuda.synchronize()
     assert torch.equal(before, cache.pool)
+
+
+def test_late_dominant_key_redoes_the_segment_with_the_exact_max():
+    """The reference max of a segment is taken from its first tile.  A key far later whose
+    logit exceeds it by hundreds overflows the fp32 weights, which the kernel must detect and
+    repair by redoing the segment with the exact max: the output is then that key's value row."""
+    G = _harness()
+    w = W.custom_workload("dominant", 77, "bf16", 1, 2, 64, 16, [700, 90, 300], [20, 3, 40])
+    data = draw_step_data(w)
+    for u, tok in ((0, 555), (2, 37)):                 # small logits everywhere, one huge key
+        h = np.array(data["hist"][0][u])
+        h[0] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(h[0]) * 0.01)
+        h[0, tok] = W.f32_to_bf16_bits(np.full((w.heads, w.head_dim), 60.0, np.float32))
+        data["hist"][0][u] = h
+    lo, hi = w.new_indptr[0], w.new_indptr[1]
+    lo2, hi2 = w.new_indptr[2], w.new_indptr[3]
+    q = W.bf16_bits_to_f32(data["q"][0]).copy()
+    q[lo:hi] = np.abs(q[lo:hi]) + 0.5                  # positive queries: logit = 60 * sum(q) / 8 >> 100
+    q[lo2:hi2] = np.abs(q[lo2:hi2]) + 0.5
+    data["q"][0] = W.f32_to_bf16_bits(q)
+    step = G.GpuStep(w, fill_byte=FILL)
+    store = _oracle_store(w, data)
+    step.unpack_histories(data, 0)
+    step.append(data, 0)
+    got = step.attention(data, 0)
+    ref = oracle.attn_incremental(store, 0, data["q"][0], w.page_indptr, w.page_indices,
+                                  w.prefix_lens, w.new_indptr)
+    check_attention(w, got, ref)
+    # sanity of the construction: the dominant key really takes all the weight
+    assert np.allclose(ref[lo:hi, 0], as_values(data["hist"][0][0][1, 555, 0]), atol=1e-6)
