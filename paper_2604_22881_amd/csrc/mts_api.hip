@@ -125,6 +125,12 @@ AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   p.q_tile = 16; p.q_tiles_max = 1; p.n_items = 0; p.min_tiles = 4; p.max_waves = 4;
   if (!p.use_mfma || b.total_new <= 0 || b.batch <= 0) return p;
   const int max_new = b.max_new > 0 ? b.max_new : 1;
+  // Long new segments (a cache miss, Sec. 5.1's full prefill) are a dense contraction: the
+  // workgroup-per-query-block kernel shares K/V tiles through LDS and needs no workspace.
+  // Short ones with long prefixes need the split-kv schedule of the streaming kernel.
+  bool prefill = max_new >= 256 && (int64_t)b.total_new >= 128ll * b.batch;
+  if (const char* env = getenv("MTS_ATTN_PREFILL")) prefill = atoi(env) != 0;
+  if (prefill && attn_prefill_applicable(g, b)) { p.use_prefill = true; return p; }
   p.q_tile = roundup(max_new, 16) < 64 ? roundup(max_new, 16) : 64;
   p.q_tiles_max = (max_new + p.q_tile - 1) / p.q_tile;
   const int64_t items = (int64_t)b.batch * p.q_tiles_max;
@@ -265,6 +271,8 @@ int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const v
   }
   const float scale = sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)g.D);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (plan.use_mfma && plan.use_prefill && !getenv("MTS_ATTN_PLAIN"))
+    return hip_status(mts::launch_attn_prefill(g, q, out, b, scale, s), "mts_attn_incremental launch");
   if (plan.use_mfma && !getenv("MTS_ATTN_PLAIN"))
     return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, plan.ws_bytes > 0 ? workspace : nullptr, s),
                       "mts_attn_incremental launch");

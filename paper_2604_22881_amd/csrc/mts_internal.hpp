@@ -38,6 +38,7 @@ hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new
 // Shape plan of one attention call: computed on the host from the scalar bounds only.
 struct AttnPlan {
   bool    use_mfma;      // bf16 matrix-core kernel, else the plain fp32-accumulate kernel
+  bool    use_prefill;   // workgroup-per-query-block kernel for long new segments (no workspace)
   bool    too_large;     // more (user, query tile) items than the schedule can hold
   int32_t q_tile;        // queries per query tile (multiple of 16, <= 64)
   int32_t q_tiles_max;   // ceil(max_new / q_tile)
@@ -50,6 +51,9 @@ struct AttnPlan {
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b);
 
 hipError_t launch_attn_generic(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
+                               float sm_scale, hipStream_t stream);
+bool attn_prefill_applicable(const PoolGeom& g, const BatchDev& b);
+hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
                                float sm_scale, hipStream_t stream);
 hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
                             const BatchDev& b, float sm_scale, void* workspace, hipStream_t stream);

@@ -37,7 +37,7 @@ def _sample_users(w, rng, count):
 
 
 @pytest.mark.parametrize("name,n_users,n_heads", [("batched_incremental", 8, 3), ("long_history", 4, 2),
-                                                  ("host_staging", 6, 2)])
+                                                  ("host_staging", 6, 2), ("miss_prefill", 2, 2)])
 def test_sampled_pairs_match_oracle(name, n_users, n_heads):
     torch, G, w, step = _setup(name)
     rng = np.random.default_rng([w.seed, 5])

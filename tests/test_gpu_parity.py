@@ -138,6 +138,55 @@ def test_attention_small(name, schedule, monkeypatch):
         check_attention(w, got, ref)
 
 
+PREFILL_CASES = {
+    # long new segments: the workgroup-per-query-block kernel is chosen by the library itself
+    "prefill_d64": ("bf16", 1, 3, 64, 16, [100, 0, 37], [300, 520, 257], 1024),
+    "prefill_d128_s32": ("bf16", 1, 2, 128, 32, [0, 70], [600, 256], 1024),
+    "prefill_d128_s64": ("bf16", 1, 2, 128, 64, [513], [449], 1024),
+    "prefill_mixed_lengths": ("bf16", 1, 2, 64, 16, [0, 900, 15, 64], [1025, 1, 31, 129], 1024),
+}
+# short and ragged segments through the same kernel, forced on
+FORCED_PREFILL = ["bf16_ragged", "bf16_d128_s32", "bf16_multi_qtile", "bf16_empty_users"]
+
+
+def _attention_matches_oracle(w):
+    G = _harness()
+    data = draw_step_data(w)
+    step = G.GpuStep(w, fill_byte=FILL)
+    store = _oracle_store(w, data)
+    for l in range(w.layers):
+        step.unpack_histories(data, l)
+        step.append(data, l)
+        got = step.attention(data, l)
+        ref = oracle.attn_incremental(store, l, data["q"][l], w.page_indptr, w.page_indices,
+                                      w.prefix_lens, w.new_indptr)
+        check_attention(w, got, ref)
+
+
+@pytest.mark.parametrize("name", list(PREFILL_CASES))
+def test_attention_long_new_segments(name):
+    """Blocks of 256 queries per workgroup: several blocks per user, a ragged last block,
+    wavefronts without queries, prefixes that end inside a tile."""
+    dtype, L, H, D, S, prefix, new, chunk = PREFILL_CASES[name]
+    _attention_matches_oracle(W.custom_workload(name, 200 + len(name), dtype, L, H, D, S, prefix, new,
+                                                chunk_tokens=chunk))
+
+
+@pytest.mark.parametrize("name", FORCED_PREFILL)
+def test_attention_small_through_the_prefill_kernel(name, monkeypatch):
+    monkeypatch.setenv("MTS_ATTN_PREFILL", "1")
+    _attention_matches_oracle(_case(name))
+
+
+@pytest.mark.parametrize("name", ["prefill_d64", "prefill_d128_s32"])
+def test_long_new_segments_through_the_streaming_kernel(name, monkeypatch):
+    """The two matrix-core kernels are interchangeable: the same cases with the other one."""
+    monkeypatch.setenv("MTS_ATTN_PREFILL", "0")
+    dtype, L, H, D, S, prefix, new, chunk = PREFILL_CASES[name]
+    _attention_matches_oracle(W.custom_workload(name, 200 + len(name), dtype, L, H, D, S, prefix, new,
+                                                chunk_tokens=chunk))
+
+
 def test_tiny_reuse_config_matches_oracle_and_recompute():
     """BASELINE config 1 (1 user, L2 H4 D32 fp32, prefix 256 + 16 new, block 16)."""
     G = _harness()
@@ -193,10 +242,14 @@ def test_empty_batch_and_no_new_tokens_are_noops():
     assert torch.equal(before, cache.pool)
 
 
-def test_late_dominant_key_redoes_the_segment_with_the_exact_max():
-    """The reference max of a segment is taken from its first tile.  A key far later whose
+@pytest.mark.parametrize("prefill", [None, "1"])
+def test_late_dominant_key_redoes_the_segment_with_the_exact_max(prefill, monkeypatch):
+    """Both matrix-core kernels (streaming; workgroup-per-query-block, forced on).
+    The reference max of a segment is taken from its first tile.  A key far later whose
     logit exceeds it by hundreds overflows the fp32 weights, which the kernel must detect and
     repair by redoing the segment with the exact max: the output is then that key's value row."""
+    if prefill is not None:
+        monkeypatch.setenv("MTS_ATTN_PREFILL", prefill)
     G = _harness()
     w = W.custom_workload("dominant", 77, "bf16", 1, 2, 64, 16, [700, 90, 300], [20, 3, 40])
     data = draw_step_data(w)
