@@ -411,7 +411,7 @@ hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, cons
   uint16_t* op = reinterpret_cast<uint16_t*>(out);
   switch (g.D) {
     case 64: return launch_one<64, 3, 2>(g, b, qp, op, c, q_blocks_max, id_bytes, stream);
-    case 128: return launch_one<128, 3, 1>(g, b, qp, op, c, q_blocks_max, id_bytes, stream);
+    case 128: return launch_one<128, 2, 1>(g, b, qp, op, c, q_blocks_max, id_bytes, stream);
     default: return hipErrorInvalidValue;
   }
 }
