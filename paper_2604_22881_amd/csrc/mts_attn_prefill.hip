@@ -3,8 +3,8 @@
 // recompute baseline, Sec. 5.1), laid out for the case of MANY new tokens per user, where the
 // work is a dense contraction and K/V reuse across queries decides the speed.
 //
-// A workgroup (4 wavefronts) owns one (user, head, block of 256 new tokens): wavefront w takes
-// the 64 queries 64*w .. 64*w+63 of the block.  All four walk the same kv tiles, so each
+// A workgroup (4 wavefronts) owns one (user, head, block of 4*16*NQB new tokens): wavefront w
+// takes queries 16*NQB*w .. 16*NQB*(w+1)-1 of the block.  All four walk the same kv tiles, so each
 // 32-token K/V tile is fetched from global memory ONCE per workgroup: every wavefront loads a
 // quarter of the tile's 16-byte MFMA fragments, parks them in LDS in fragment order (lane l of
 // fragment f at f*1 KiB + l*16 B: reads and writes are conflict-free), and after one barrier
@@ -33,8 +33,6 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;   // one 16-byte fragment
 
 constexpr int kTile = 32;        // kv tokens per step
-constexpr int kBlockQ = 256;     // new tokens per workgroup
-constexpr int kNQB = 4;          // 16-query blocks per wavefront
 constexpr int kXcds = 8;
 constexpr int kMaxIdBytes = 64 * 1024;   // LDS page table of one block
 
@@ -50,11 +48,13 @@ __device__ __forceinline__ float quad_row_max(float v) {
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-template <int D, int PFD, int WPS>
+template <int D, int PFD, int WPS, int kNQB>
 __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, BatchDev b,
                                                                 const uint16_t* __restrict__ q,
                                                                 uint16_t* __restrict__ out, float c,
                                                                 int q_blocks_max, int n_pairs, int id_cap) {
+  constexpr int kWaveQ = 16 * kNQB;    // queries per wavefront
+  constexpr int kBlockQ = 4 * kWaveQ;  // new tokens per workgroup
   constexpr int KS = D / 32;           // k-steps of Q.K
   constexpr int DB = D / 16;           // 16-dim blocks of the output
   constexpr int FR = 2 * KS + DB;      // 16-byte fragments per lane and tile: K (half, step), then V (dim block)
@@ -88,9 +88,9 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
 
   const int blk_end = (n_u < Q0 + kBlockQ) ? n_u : (Q0 + kBlockQ);
   const int tiles_wg = (P + blk_end + kTile - 1) / kTile;      // kv tiles the block's last query sees
-  const int q0 = Q0 + 64 * wave;                                // this wavefront's queries
+  const int q0 = Q0 + kWaveQ * wave;                                // this wavefront's queries
   int nq = n_u - q0;
-  nq = nq < 0 ? 0 : (nq > 64 ? 64 : nq);
+  nq = nq < 0 ? 0 : (nq > kWaveQ ? kWaveQ : nq);
   const int tiles_w = nq > 0 ? (P + q0 + nq + kTile - 1) / kTile : 0;
   const int first_query_pos = P + q0;
 
@@ -371,10 +371,13 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
   }
 }
 
-template <int D, int PFD, int WPS>
+template <int D, int PFD, int WPS, int NQB>
 hipError_t launch_one(const PoolGeom& g, const BatchDev& b, const uint16_t* q, uint16_t* out, float c,
-                      int q_blocks_max, int64_t id_bytes, hipStream_t stream) {
-  auto kern = attn_prefill_kernel<D, PFD, WPS>;
+                      int64_t id_bytes, hipStream_t stream) {
+  auto kern = attn_prefill_kernel<D, PFD, WPS, NQB>;
+  constexpr int kBlockQ = 64 * NQB;
+  int q_blocks_max = (b.max_new + kBlockQ - 1) / kBlockQ;
+  if (q_blocks_max < 1) q_blocks_max = 1;
   static bool attr_set = false;                                  // static + dynamic LDS may pass 64 KiB
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -403,15 +406,16 @@ hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, cons
   if (b.total_new <= 0 || b.batch <= 0) return hipSuccess;
   if (!attn_prefill_applicable(g, b)) return hipErrorInvalidValue;
   const float c = sm_scale * 1.4426950408889634f;     // logits are exponentiated in base 2
-  int q_blocks_max = (b.max_new + kBlockQ - 1) / kBlockQ;
-  if (q_blocks_max < 1) q_blocks_max = 1;
   // table entries one block may touch: its tiles end at most one tile past max_total_len
   const int64_t id_bytes = (((int64_t)b.max_total_len + g.S - 1) / g.S + 4) * 4;
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(q);
   uint16_t* op = reinterpret_cast<uint16_t*>(out);
+  // Two wavefronts per SIMD in both shapes (<= 256 registers each): one wavefront alone issues
+  // in order and leaves its LDS operand reads and MFMA -> VALU dependencies exposed.  At
+  // D = 128 that means 32 queries per wavefront (64-register accumulator) and 128-query blocks.
   switch (g.D) {
-    case 64: return launch_one<64, 3, 2>(g, b, qp, op, c, q_blocks_max, id_bytes, stream);
-    case 128: return launch_one<128, 2, 1>(g, b, qp, op, c, q_blocks_max, id_bytes, stream);
+    case 64: return launch_one<64, 3, 2, 4>(g, b, qp, op, c, id_bytes, stream);
+    case 128: return launch_one<128, 2, 2, 2>(g, b, qp, op, c, id_bytes, stream);
     default: return hipErrorInvalidValue;
   }
 }
