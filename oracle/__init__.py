@@ -6,7 +6,9 @@ may import it.  It shares no code, tables or helpers with the HIP path and is
 written directly from the paper's statement of the method.
 
 Pinned functions (see tests/test_oracle_*.py): page arithmetic, unpack, append,
-pack, attn_incremental, full_recompute.  No function here is "parity unpinned".
+pack, attn_incremental, full_recompute, attn_pointwise, full_recompute_pointwise.
+No function here is "parity unpinned"; attn_pointwise follows a definition this build
+states itself (the paper prints none), and its pins hold it to that definition.
 """
 from .mts_oracle import (  # noqa: F401
     PagedStore,
@@ -21,4 +23,6 @@ from .mts_oracle import (  # noqa: F401
     pack,
     attn_incremental,
     full_recompute,
+    attn_pointwise,
+    full_recompute_pointwise,
 )

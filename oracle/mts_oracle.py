@@ -24,6 +24,15 @@ What is modelled, and where the paper defines it:
   over all T tokens on contiguous tensors, knowing nothing of pages ->
   :func:`full_recompute`.  Reuse must reproduce its last ``T - P_pre`` rows.
 
+* The pointwise variant of the same step -> :func:`attn_pointwise` and
+  :func:`full_recompute_pointwise`.  Sec. 2 (Eq. 1-3) takes its backbone from
+  the HSTU line of work and leaves ``Attention`` undefined; that line of work
+  aggregates with an elementwise SiLU of the scaled logits and a length
+  normaliser instead of a softmax.  The definition used here,
+  ``o_i = inv_norm * sum_{j<=p_i} silu(s * q_i . k_j) v_j``, is this build's
+  statement of it (the paper prints no formula): parity of the GPU path is
+  per this definition.
+
 Readings taken where the paper is silent: ``Attention`` is scaled-dot-product
 softmax attention with scale 1/sqrt(D) unless given; no positional bias; one
 head count for Q, K and V; causal order among the new tokens and full view of
@@ -244,4 +253,63 @@ def full_recompute(q, k, v, sm_scale=None) -> np.ndarray:
             for j in range(p + 1):
                 acc += (weights[j] / total) * vv[j, h]
             out[p, h] = acc
+    return out
+
+
+def _silu(z: np.ndarray) -> np.ndarray:
+    """x * sigmoid(x), written so that neither branch overflows."""
+    e = np.exp(-np.abs(z))
+    return np.where(z >= 0, z / (1.0 + e), z * e / (1.0 + e))
+
+
+def attn_pointwise(store: PagedStore, layer: int, q, page_indptr, page_indices,
+                   prefix_lens, new_indptr, inv_norm, sm_scale=None, users=None, heads=None) -> np.ndarray:
+    """Pointwise-aggregated variant of :func:`attn_incremental` (Sec. 2, Eq. 3 with the
+    HSTU-style aggregation; see the module docstring for the definition taken).
+
+    For user u, head h and new token i at absolute position p = P_u + i:
+    ``o = inv_norm * sum_{j in [0, p]} silu(s * q_i . K_j) V_j``; rows are read from
+    the pages exactly as in the softmax form.  ``inv_norm`` is one scalar for the call.
+    """
+    D, H = store.D, store.H
+    s = (1.0 / math.sqrt(D)) if sm_scale is None else float(sm_scale)
+    qv = decode_values(q)
+    out = np.full(qv.shape, np.nan, dtype=np.float64)
+    B = len(prefix_lens)
+    for u in (range(B) if users is None else users):
+        P = int(prefix_lens[u])
+        lo, hi = int(new_indptr[u]), int(new_indptr[u + 1])
+        n = hi - lo
+        if n == 0:
+            continue
+        T = P + n
+        pages = np.asarray(page_indices[page_indptr[u]:page_indptr[u + 1]])
+        _check_run(store, pages, 0, T)
+        need = pages[: pages_for(T, store.S)]
+        kv = store.data[layer, need]                      # [pages][2][S][H][D]
+        K = decode_values(kv[:, 0].reshape(-1, H, D)[:T])
+        V = decode_values(kv[:, 1].reshape(-1, H, D)[:T])
+        pos = P + np.arange(n)[:, None]
+        hidden = np.arange(T)[None, :] > pos              # key after the query
+        for h in (range(H) if heads is None else heads):
+            w = _silu(s * (qv[lo:hi, h] @ K[:, h].T))     # [n][T]
+            w[hidden] = 0.0
+            out[lo:hi, h] = float(inv_norm) * (w @ V[:, h])
+    return out
+
+
+def full_recompute_pointwise(q, k, v, inv_norm, sm_scale=None) -> np.ndarray:
+    """The pointwise form over a whole contiguous sequence, term by term (no pages, no
+    matrix form): token p aggregates tokens 0..p.  Reuse must match its last rows."""
+    qv, kv, vv = decode_values(q), decode_values(k), decode_values(v)
+    T, H, D = qv.shape
+    s = (1.0 / math.sqrt(D)) if sm_scale is None else float(sm_scale)
+    out = np.zeros((T, H, D), dtype=np.float64)
+    for h in range(H):
+        for p in range(T):
+            acc = np.zeros(D)
+            for j in range(p + 1):
+                x = s * float(np.dot(qv[p, h], kv[j, h]))
+                acc += (x / (1.0 + math.exp(-x)) if x > -700.0 else 0.0) * vv[j, h]
+            out[p, h] = float(inv_norm) * acc
     return out
