@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="batched_incremental")
+    ap.add_argument("--attention", choices=("softmax", "pointwise"), default="softmax",
+                    help="aggregation: mts_attn_incremental (default) or mts_attn_pointwise")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
     ap.add_argument("--no-miss", action="store_true", help="diagnostic: no restored users (no unpack, no per-layer wait)")
@@ -54,7 +56,7 @@ def attention_flops_per_layer(w):
     return 4 * w.head_dim * w.heads * pairs
 
 
-def cpu_baseline(w, budget_s=12.0):
+def cpu_baseline(w, budget_s=12.0, pointwise=False):
     """The oracle, as it stands, on a bounded sample of the same workload: whole users (all
     heads), one layer's worth of work per pass - unpack of the history in host-chunk runs,
     append, attention - repeated over fresh data until about `budget_s` seconds of CPU work."""
@@ -81,7 +83,11 @@ def cpu_baseline(w, budget_s=12.0):
         for start, cnt in W.host_chunks(P, w.chunk_tokens):
             oracle.unpack(store, 0, hist[:, start:start + cnt], sub.user_pages(0), start)
         oracle.append(store, 0, k, v, sub.page_indptr, sub.page_indices, sub.prefix_lens, sub.new_indptr)
-        oracle.attn_incremental(store, 0, q, sub.page_indptr, sub.page_indices, sub.prefix_lens, sub.new_indptr)
+        if pointwise:
+            oracle.attn_pointwise(store, 0, q, sub.page_indptr, sub.page_indices, sub.prefix_lens,
+                                  sub.new_indptr, 1.0 / max(1, P + n))
+        else:
+            oracle.attn_incremental(store, 0, q, sub.page_indptr, sub.page_indices, sub.prefix_lens, sub.new_indptr)
         t_used += time.perf_counter() - t0
         layer_tokens += n
         passes += 1
@@ -143,6 +149,9 @@ def main():
     ev_appended = [torch.cuda.Event() for _ in range(L)]
     cs, ss = compute.cuda_stream, side.cuda_stream
 
+    pointwise = args.attention == "pointwise"
+    inv_norm = 1.0 / max(1, int(w.total_lens.max()))
+
     def step(attn_events=None):
         for l in range(L):
             if miss_segs.num_segs:
@@ -156,7 +165,10 @@ def main():
             if attn_events is not None:
                 a, b = attn_events[l]
                 a.record(compute)
-            mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=cs)
+            if pointwise:
+                mts.mts_attn_pointwise(cache.desc, l, q[l], out[l], batch.meta, inv_norm, 0.0, ws, ws_bytes, stream=cs)
+            else:
+                mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=cs)
             if attn_events is not None:
                 b.record(compute)
             if evict_segs.num_segs:
@@ -225,11 +237,12 @@ def main():
         "config": {"workload": w.name, "seed": w.seed, "users": w.batch, "layers": L, "heads": H,
                    "head_dim": D, "page_size": w.page_size, "prefix_tokens": int(w.prefix_lens.sum()),
                    "new_tokens": N, "miss_users": len(miss), "evict_users": len(evict),
-                   "pool_pages": w.num_pages},
+                   "pool_pages": w.num_pages, "attention": args.attention},
         "kv_read_gbps_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
         "kv_read_frac_of_peak_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "attention_tflops": flops / (attn_ms_avg * 1e-3) / 1e12,
-        "roofline": {"kernel": "mts_attn_incremental (attention kernel + split-kv merge)",
+        "roofline": {"kernel": ("mts_attn_pointwise" if pointwise else "mts_attn_incremental") +
+                               " (attention kernel + split-kv merge)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "bytes_per_launch": alg_bytes, "avg_launch_ms": attn_ms_avg},
@@ -242,11 +255,11 @@ def main():
                                 "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS,
                                 "flops_per_launch": flops})
     traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(traffic_file):          # measured HBM bytes per launch, from rocprofv3 --pmc runs
+    if os.path.exists(traffic_file) and not pointwise:          # measured HBM bytes per launch, from rocprofv3 --pmc runs
         with open(traffic_file) as f:
             res["roofline"]["traffic"] = json.load(f).get("hbm_bytes_per_launch")
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w)
+        res["cpu_baseline"] = cpu_baseline(w, pointwise=pointwise)
     print(json.dumps(res))
 
 

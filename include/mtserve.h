@@ -166,6 +166,22 @@ int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const v
                              void* out, const mts_batch_meta* meta, float sm_scale,
                              void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * Pointwise-aggregated variant of mts_attn_incremental: the same queries, keys, visibility and
+ * paged reads, with the aggregation of the HSTU-style backbone the paper serves (Sec. 2, Eq. 1-3;
+ * the paper prints no formula for its Attention, so this header states the one computed):
+ *     out[i, h, :] = inv_norm * sum_j silu(sm_scale * q[i, h, :] . K[j, h, :]) * V[j, h, :],  j in [0, p]
+ * with silu(x) = x / (1 + exp(-x)).  No softmax statistics exist, so split-kv pieces simply add.
+ *   sm_scale   logit scale; 0 selects 1/sqrt(D)
+ *   inv_norm   normaliser, finite and > 0 (e.g. 1 / longest sequence of the batch)
+ * Everything else (arguments, workspace from mts_attn_workspace_bytes, preconditions, errors,
+ * precision: fp32 logits and accumulators, weights rounded to bf16 for the matrix cores) is as
+ * for mts_attn_incremental.
+ */
+int32_t mts_attn_pointwise(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
+                           const mts_batch_meta* meta, float sm_scale, float inv_norm,
+                           void* workspace, int64_t workspace_bytes, void* stream);
+
 /* Host<->device staging copies on `stream` (hipMemcpyAsync); `host` should be pinned for the
  * copy to be asynchronous (Sec. 4.2, DMA between pinned buffers and the onload / offload buffers). */
 int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream);

@@ -19,7 +19,7 @@ MTS_F32, MTS_BF16 = 0, 1
 
 EXPORTS = (
     "mts_page_bytes", "mts_pages_for", "mts_elem_offset", "mts_kv_unpack", "mts_kv_pack",
-    "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental",
+    "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_pointwise",
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
 )
 
@@ -66,6 +66,7 @@ def lib():
         "mts_kv_append": (I32, [DESC, I32, P, P, META, P]),
         "mts_attn_workspace_bytes": (I64, [DESC, META]),
         "mts_attn_incremental": (I32, [DESC, I32, P, P, META, F32, P, I64, P]),
+        "mts_attn_pointwise": (I32, [DESC, I32, P, P, META, F32, F32, P, I64, P]),
         "mts_stage_h2d_async": (I32, [P, P, I64, P]),
         "mts_stage_d2h_async": (I32, [P, P, I64, P]),
         "mts_last_error": (C.c_char_p, []),
@@ -154,6 +155,13 @@ def mts_attn_incremental(desc, layer, q, out, meta, sm_scale=0.0, workspace=None
     return _check(lib().mts_attn_incremental(C.byref(desc), layer, _ptr(q), _ptr(out), C.byref(meta),
                                              float(sm_scale), _ptr(workspace), int(workspace_bytes),
                                              _stream(stream)))
+
+
+def mts_attn_pointwise(desc, layer, q, out, meta, inv_norm, sm_scale=0.0, workspace=None, workspace_bytes=0,
+                       stream=None):
+    return _check(lib().mts_attn_pointwise(C.byref(desc), layer, _ptr(q), _ptr(out), C.byref(meta),
+                                           float(sm_scale), float(inv_norm), _ptr(workspace),
+                                           int(workspace_bytes), _stream(stream)))
 
 
 def mts_stage_h2d_async(device_dst, host_src, nbytes, stream=None):

@@ -245,9 +245,14 @@ int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_me
   return plan.ws_bytes;
 }
 
-int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
-                             const mts_batch_meta* meta, float sm_scale, void* workspace,
-                             int64_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// mts_attn_incremental (inv_norm == 0) and mts_attn_pointwise (inv_norm > 0)
+int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
+                       const mts_batch_meta* meta, float sm_scale, float inv_norm, void* workspace,
+                       int64_t workspace_bytes, void* stream) {
   mts::PoolGeom g{};
   mts::BatchDev b{};
   int32_t st;
@@ -272,11 +277,31 @@ int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const v
   const float scale = sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)g.D);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (plan.use_mfma && plan.use_prefill && !getenv("MTS_ATTN_PLAIN"))
-    return hip_status(mts::launch_attn_prefill(g, q, out, b, scale, s), "mts_attn_incremental launch");
+    return hip_status(mts::launch_attn_prefill(g, q, out, b, scale, inv_norm, s), name);
   if (plan.use_mfma && !getenv("MTS_ATTN_PLAIN"))
-    return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, plan.ws_bytes > 0 ? workspace : nullptr, s),
-                      "mts_attn_incremental launch");
-  return hip_status(mts::launch_attn_generic(g, q, out, b, scale, s), "mts_attn_incremental launch");
+    return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, inv_norm, plan.ws_bytes > 0 ? workspace : nullptr, s),
+                      name);
+  return hip_status(mts::launch_attn_generic(g, q, out, b, scale, inv_norm, s), name);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
+                             const mts_batch_meta* meta, float sm_scale, void* workspace,
+                             int64_t workspace_bytes, void* stream) {
+  return attention_call("mts_attn_incremental launch", cache, layer, q, out, meta, sm_scale, 0.f, workspace,
+                        workspace_bytes, stream);
+}
+
+int32_t mts_attn_pointwise(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
+                           const mts_batch_meta* meta, float sm_scale, float inv_norm, void* workspace,
+                           int64_t workspace_bytes, void* stream) {
+  if (!(inv_norm > 0.f) || inv_norm > 1e30f)
+    return fail(MTS_ERR_INVALID_ARG, "inv_norm must be finite and > 0");
+  return attention_call("mts_attn_pointwise launch", cache, layer, q, out, meta, sm_scale, inv_norm, workspace,
+                        workspace_bytes, stream);
 }
 
 int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream) {

@@ -1,5 +1,6 @@
 // Plain incremental attention (Sec. 2, Eq. 6-7): one wavefront per (new token, head),
-// fp32 logits, running-max softmax and fp32 accumulation, no matrix cores.  It serves the
+// fp32 logits, running-max softmax and fp32 accumulation, no matrix cores.  PW selects the
+// pointwise aggregation instead (silu of the scaled logit, times a normaliser; no softmax).  It serves the
 // fp32 element type (the reuse-versus-recompute check shape) and is the slow, simple path
 // for bf16 shapes the matrix-core kernel does not take.
 #include <math.h>
@@ -31,10 +32,10 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-template <typename T>
+template <typename T, bool PW>
 __global__ __launch_bounds__(64) void attn_generic_kernel(PoolGeom g, BatchDev b,
                                                           const T* __restrict__ q,
-                                                          T* __restrict__ out, float scale) {
+                                                          T* __restrict__ out, float scale, float inv_norm) {
   constexpr int G = 16 / sizeof(T);
   const int tok = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   const int H = g.H, D = g.D, S = g.S;
@@ -73,13 +74,18 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(PoolGeom g, BatchDev b
         z = dot * scale;
       }
     }
-    const float m_new = fmaxf(m, wave_max(z));        // finite: token `base` is always visible
-    const float p = expf(z - m_new);
-    const float alpha = expf(m - m_new);
-    l = l * alpha + wave_sum(p);
-    acc0 *= alpha;
-    acc1 *= alpha;
-    m = m_new;
+    float p;
+    if (PW) {
+      p = (z == -INFINITY) ? 0.f : z / (1.0f + expf(-z));      // silu; hidden or absent keys weigh 0
+    } else {
+      const float m_new = fmaxf(m, wave_max(z));        // finite: token `base` is always visible
+      p = expf(z - m_new);
+      const float alpha = expf(m - m_new);
+      l = l * alpha + wave_sum(p);
+      acc0 *= alpha;
+      acc1 *= alpha;
+      m = m_new;
+    }
     ps[lane] = p;
     __syncthreads();
     const int cnt = (kv_len - base) < 64 ? (kv_len - base) : 64;
@@ -99,22 +105,24 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(PoolGeom g, BatchDev b
     __syncthreads();
   }
   T* o = out + ((int64_t)tok * H + h) * D;
-  if (lane < D) store_elem(o + lane, acc0 / l);
-  if (lane + 64 < D) store_elem(o + lane + 64, acc1 / l);
+  if (lane < D) store_elem(o + lane, PW ? acc0 * inv_norm : acc0 / l);
+  if (lane + 64 < D) store_elem(o + lane + 64, PW ? acc1 * inv_norm : acc1 / l);
 }
 
 }  // namespace
 
 hipError_t launch_attn_generic(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
-                               float sm_scale, hipStream_t stream) {
+                               float sm_scale, float inv_norm, hipStream_t stream) {
   if (b.total_new <= 0) return hipSuccess;
   dim3 grid((unsigned)b.total_new, (unsigned)g.H, 1), block(64, 1, 1);
-  if (g.es == 2)
-    hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, block, 0, stream, g, b,
-                       (const uint16_t*)q, (uint16_t*)out, sm_scale);
-  else
-    hipLaunchKernelGGL(attn_generic_kernel<uint32_t>, grid, block, 0, stream, g, b,
-                       (const uint32_t*)q, (uint32_t*)out, sm_scale);
+  const bool pw = inv_norm > 0.f;
+  if (g.es == 2) {
+    auto kern = pw ? attn_generic_kernel<uint16_t, true> : attn_generic_kernel<uint16_t, false>;
+    hipLaunchKernelGGL(kern, grid, block, 0, stream, g, b, (const uint16_t*)q, (uint16_t*)out, sm_scale, inv_norm);
+  } else {
+    auto kern = pw ? attn_generic_kernel<uint32_t, true> : attn_generic_kernel<uint32_t, false>;
+    hipLaunchKernelGGL(kern, grid, block, 0, stream, g, b, (const uint32_t*)q, (uint32_t*)out, sm_scale, inv_norm);
+  }
   return hipGetLastError();
 }
 

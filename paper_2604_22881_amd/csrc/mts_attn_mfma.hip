@@ -30,6 +30,11 @@
 // Row sums come from the matrix core (a ones fragment times P^T).  Should the first tile have
 // been so unrepresentative that a denominator overflows, the segment is redone with the exact
 // max, found by a K-only pass.
+//
+// Pointwise mode (template flag PW).  The same schedule, operand flow and pipeline serve the
+// pointwise aggregation out = inv_norm * sum_j silu(c * q.k_j) v_j: the weights need no
+// statistics at all, so there is no reference max, no denominator and no redo; hidden keys
+// get logit 0 (silu(0) = 0); cut pairs are finished by adding their pieces.
 #include <math.h>
 
 #include <type_traits>
@@ -50,6 +55,10 @@ constexpr int kWavesPerWg = 4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+// x * sigmoid(x); -inf never reaches it (hidden keys carry logit 0 in pointwise mode)
+__device__ __forceinline__ float fast_silu(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + fast_exp2(-1.4426950408889634f * x));
+}
 
 // max over the 4 lanes that hold the same query (lane, lane^16, lane^32, lane^48)
 __device__ __forceinline__ float quad_row_max(float v) {
@@ -84,10 +93,10 @@ struct MergeDesc {
 };
 
 // WPS = wavefronts per SIMD the kernel is compiled for (bounds its registers)
-template <int D, int NQB, int PF, int WPS>
+template <int D, int NQB, int PF, int WPS, bool PW>
 __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, BatchDev b,
                                                           const uint16_t* __restrict__ q,
-                                                          uint16_t* __restrict__ out, float c,
+                                                          uint16_t* __restrict__ out, float c, float inv_norm,
                                                           int q_tiles_max, int n_items, int min_tiles,
                                                           MergeDesc* __restrict__ ws_desc,
                                                           float* __restrict__ ws_o,
@@ -285,8 +294,8 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         const int kbase = tb + 8 * gq;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if (kbase + e > qpos) s0[e] = -INFINITY;
-          if (kbase + 4 + e > qpos) s1[e] = -INFINITY;
+          if (kbase + e > qpos) s0[e] = PW ? 0.f : -INFINITY;
+          if (kbase + 4 + e > qpos) s1[e] = PW ? 0.f : -INFINITY;
         }
       }
     };
@@ -323,14 +332,19 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          pf[e] = (__bf16)fast_exp2(fmaf(s0[e], c, -mcq[qb]));
-          pf[4 + e] = (__bf16)fast_exp2(fmaf(s1[e], c, -mcq[qb]));
+          if constexpr (PW) {
+            pf[e] = (__bf16)fast_silu(s0[e] * c);
+            pf[4 + e] = (__bf16)fast_silu(s1[e] * c);
+          } else {
+            pf[e] = (__bf16)fast_exp2(fmaf(s0[e], c, -mcq[qb]));
+            pf[4 + e] = (__bf16)fast_exp2(fmaf(s1[e], c, -mcq[qb]));
+          }
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db)
           o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][db], pf, o[db][qb], 0, 0, 0);
         // row sums of the (rounded) weights on the matrix core: every row of ones . P^T
-        lacc[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf, lacc[qb], 0, 0, 0);
+        if constexpr (!PW) lacc[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf, lacc[qb], 0, 0, 0);
       }
     };
 
@@ -384,7 +398,9 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
 #pragma unroll
           for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        if (attempt == 1) exact_max(nq_c);
+        if constexpr (!PW) {
+          if (attempt == 1) exact_max(nq_c);
+        }
 
         page_ids(t_beg, idr0[0], idr1[0]);
         if constexpr (PF > 1) page_ids(t_beg + 1, idr0[1], idr1[1]);
@@ -395,7 +411,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         if constexpr (PF > 2) issue(std::integral_constant<int, 2>{}, t_beg + 2);
         if constexpr (PF > 3) issue(std::integral_constant<int, 3>{}, t_beg + 3);
 
-        if (attempt == 0) {
+        if (!PW && attempt == 0) {
           // reference max = max of the segment's first tile (already in ring slot 0)
           const int tb = t_beg * kTile;
 #pragma unroll
@@ -443,6 +459,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         }
 
         // A reference far below the true max shows up as an overflowed (or NaN) denominator.
+        if constexpr (PW) break;                         // no statistics, nothing to redo
         bool bad = false;
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) bad |= !(lacc[qb][0] < 1e37f);
@@ -469,7 +486,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
       for (int qb = 0; qb < NQB; ++qb) {
         const int qi = 16 * qb + r;
         if (qi < nq) {
-          const float inv = 1.0f / l[qb];
+          const float inv = PW ? inv_norm : 1.0f / l[qb];
           uint16_t* orow = out + ((int64_t)out_row + (int64_t)qi * H) * D + 4 * gq;
 #pragma unroll
           for (int db = 0; db < DB; ++db) {
@@ -490,7 +507,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
           float* po = ws_o + (prow + qi) * D + 4 * gq;
 #pragma unroll
           for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4*>(po + 16 * db) = o[db][qb];
-          if (gq == 0) {
+          if (!PW && gq == 0) {
             ws_ml[(prow + qi) * 2] = m[qb];
             ws_ml[(prow + qi) * 2 + 1] = l[qb];
           }
@@ -516,8 +533,8 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
 // whose first tile lies in share w (if that pair continues into later shares): a numerically
 // safe weighted sum of the pieces, in share order.  Share w holds its piece in slot
 // `first_slot`; every later share holds its piece as the leading one (slot 0).
-template <int D>
-__global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ out, float c, int q_tile,
+template <int D, bool PW>
+__global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ out, float c, float inv_norm, int q_tile,
                                                          int H, const MergeDesc* __restrict__ ws_desc,
                                                          const float* __restrict__ ws_o,
                                                          const float* __restrict__ ws_ml) {
@@ -539,8 +556,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ 
       const int ww = (w0 + k <= d.w_last) ? (w0 + k) : d.w_last;      // past the end: repeat, weight 0
       const int slot = (ww == w) ? d.first_slot : 0;
       const int64_t prow = ((int64_t)ww * 2 + slot) * q_tile + qi;
-      pm[k] = ws_ml[prow * 2];
-      pl[k] = ws_ml[prow * 2 + 1];
+      pm[k] = PW ? 0.f : ws_ml[prow * 2];
+      pl[k] = PW ? 0.f : ws_ml[prow * 2 + 1];
       po[k] = *reinterpret_cast<const f32x4*>(ws_o + prow * D + 4 * d4);
     }
     float Mn = M;
@@ -561,17 +578,18 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ 
     }
     M = Mn;
   }
-  const float inv = 1.0f / den;
+  // pointwise: every piece has reference 0, so the weights above are all 1 and num is the plain sum
+  const float inv = PW ? inv_norm : 1.0f / den;
   bf16x4 ob;
 #pragma unroll
   for (int k = 0; k < 4; ++k) ob[k] = (__bf16)(num[k] * inv);
   *reinterpret_cast<bf16x4*>(out + ((int64_t)d.out_row + (int64_t)qi * H) * D + 4 * d4) = ob;
 }
 
-template <int D, int NQB, int PF, int WPS>
+template <int D, int NQB, int PF, int WPS, bool PW>
 hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
-                      const BatchDev& b, float c, void* workspace, hipStream_t stream) {
-  auto kern = attn_stream_kernel<D, NQB, PF, WPS>;
+                      const BatchDev& b, float c, float inv_norm, void* workspace, hipStream_t stream) {
+  auto kern = attn_stream_kernel<D, NQB, PF, WPS, PW>;
   const size_t lds_bytes = sizeof(int) * ((size_t)3 * b.batch + 2 + plan.n_items + 1 + kWavesPerWg);
   static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
   static size_t lds_limit = 48 * 1024;
@@ -597,12 +615,12 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
   MergeDesc* ws_desc = reinterpret_cast<MergeDesc*>(ws);
   float* ws_o = reinterpret_cast<float*>(ws + plan.ws_desc_bytes);
   float* ws_ml = ws_o + (int64_t)plan.max_waves * 2 * plan.q_tile * g.D;
-  hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, out, c, plan.q_tiles_max,
+  hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, out, c, inv_norm, plan.q_tiles_max,
                      plan.n_items, plan.min_tiles, ws_desc, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_merge_kernel<D>, dim3(wgs * kWavesPerWg, (plan.q_tile * (D / 4) + 255) / 256), dim3(256), 0,
-                     stream, out, c, plan.q_tile, g.H, ws_desc, ws_o, ws_ml);
+  hipLaunchKernelGGL((attn_merge_kernel<D, PW>), dim3(wgs * kWavesPerWg, (plan.q_tile * (D / 4) + 255) / 256), dim3(256),
+                     0, stream, out, c, inv_norm, plan.q_tile, g.H, ws_desc, ws_o, ws_ml);
   return hipGetLastError();
 }
 
@@ -610,9 +628,9 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
 // wavefront covers the first one's segment start-up and overlaps its VALU work with MFMA work.
 // D = 128: the accumulators and a useful ring need more than half the register file, so one
 // wavefront per SIMD with a deeper ring (3 tiles up to 32 queries per tile, else 2).
-template <int D>
+template <int D, bool PW>
 hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
-                    const BatchDev& b, float c, void* ws, hipStream_t stream) {
+                    const BatchDev& b, float c, float inv_norm, void* ws, hipStream_t stream) {
 #ifndef MTS_PF_A
 #define MTS_PF_A 2   // D <= 64
 #define MTS_PF_B 3   // D = 128, up to 32 queries per tile
@@ -623,25 +641,36 @@ hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, 
   constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;
   constexpr int WPS = (D == 128) ? 1 : MTS_WPS_A;
   switch (plan.q_tile / 16) {
-    case 1: return launch_one<D, 1, PF_SMALL, WPS>(g, plan, q, out, b, c, ws, stream);
-    case 2: return launch_one<D, 2, PF_SMALL, WPS>(g, plan, q, out, b, c, ws, stream);
-    case 3: return launch_one<D, 3, PF_LARGE, WPS>(g, plan, q, out, b, c, ws, stream);
-    default: return launch_one<D, 4, PF_LARGE, WPS>(g, plan, q, out, b, c, ws, stream);
+    case 1: return launch_one<D, 1, PF_SMALL, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
+    case 2: return launch_one<D, 2, PF_SMALL, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
+    case 3: return launch_one<D, 3, PF_LARGE, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
+    default: return launch_one<D, 4, PF_LARGE, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
   }
 }
 
 }  // namespace
 
 hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
-                            const BatchDev& b, float sm_scale, void* workspace, hipStream_t stream) {
+                            const BatchDev& b, float sm_scale, float inv_norm, void* workspace,
+                            hipStream_t stream) {
   if (b.total_new <= 0 || b.batch <= 0) return hipSuccess;
+  if (inv_norm > 0.f) {                               // pointwise: the scale stays in natural units
+    const uint16_t* qp = reinterpret_cast<const uint16_t*>(q);
+    uint16_t* op = reinterpret_cast<uint16_t*>(out);
+    switch (g.D) {
+      case 32: return launch_d<32, true>(g, plan, qp, op, b, sm_scale, inv_norm, workspace, stream);
+      case 64: return launch_d<64, true>(g, plan, qp, op, b, sm_scale, inv_norm, workspace, stream);
+      case 128: return launch_d<128, true>(g, plan, qp, op, b, sm_scale, inv_norm, workspace, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
   const float c = sm_scale * 1.4426950408889634f;     // logits are exponentiated in base 2
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(q);
   uint16_t* op = reinterpret_cast<uint16_t*>(out);
   switch (g.D) {
-    case 32: return launch_d<32>(g, plan, qp, op, b, c, workspace, stream);
-    case 64: return launch_d<64>(g, plan, qp, op, b, c, workspace, stream);
-    case 128: return launch_d<128>(g, plan, qp, op, b, c, workspace, stream);
+    case 32: return launch_d<32, false>(g, plan, qp, op, b, c, 0.f, workspace, stream);
+    case 64: return launch_d<64, false>(g, plan, qp, op, b, c, 0.f, workspace, stream);
+    case 128: return launch_d<128, false>(g, plan, qp, op, b, c, 0.f, workspace, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -18,6 +18,9 @@
 // exact max, found by a K-only pass).  Workgroups of one (user, head) land on one XCD, longest
 // block first, so that its K/V stays in that XCD's L2 while the blocks re-read it.  Every block
 // writes its output rows itself; nothing is merged.
+//
+// PW selects the pointwise aggregation out = inv_norm * sum_j silu(c * q.k_j) v_j: no reference
+// max, no denominator, no redo; hidden keys carry logit 0 (silu(0) = 0).
 #include <math.h>
 
 #include <type_traits>
@@ -38,6 +41,9 @@ constexpr int kMaxIdBytes = 64 * 1024;   // LDS page table of one block
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float fast_silu(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + fast_exp2(-1.4426950408889634f * x));
+}
 
 __device__ __forceinline__ float quad_row_max(float v) {
   unsigned u = __float_as_uint(v);
@@ -48,10 +54,10 @@ __device__ __forceinline__ float quad_row_max(float v) {
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-template <int D, int PFD, int WPS, int kNQB>
+template <int D, int PFD, int WPS, int kNQB, bool PW>
 __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, BatchDev b,
                                                                 const uint16_t* __restrict__ q,
-                                                                uint16_t* __restrict__ out, float c,
+                                                                uint16_t* __restrict__ out, float c, float inv_norm,
                                                                 int q_blocks_max, int n_pairs, int id_cap) {
   constexpr int kWaveQ = 16 * kNQB;    // queries per wavefront
   constexpr int kBlockQ = 4 * kWaveQ;  // new tokens per workgroup
@@ -205,8 +211,8 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
       const int kbase = tb + 8 * gq;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        if (kbase + e > qpos) s0[e] = -INFINITY;
-        if (kbase + 4 + e > qpos) s1[e] = -INFINITY;
+        if (kbase + e > qpos) s0[e] = PW ? 0.f : -INFINITY;
+        if (kbase + 4 + e > qpos) s1[e] = PW ? 0.f : -INFINITY;
       }
     }
   };
@@ -220,14 +226,19 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
     bf16x8 pf;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      pf[e] = (__bf16)fast_exp2(fmaf(s0[e], c, -mcq[qb]));
-      pf[4 + e] = (__bf16)fast_exp2(fmaf(s1[e], c, -mcq[qb]));
+      if constexpr (PW) {
+        pf[e] = (__bf16)fast_silu(s0[e] * c);
+        pf[4 + e] = (__bf16)fast_silu(s1[e] * c);
+      } else {
+        pf[e] = (__bf16)fast_exp2(fmaf(s0[e], c, -mcq[qb]));
+        pf[4 + e] = (__bf16)fast_exp2(fmaf(s1[e], c, -mcq[qb]));
+      }
     }
 #pragma unroll
     for (int db = 0; db < DB; ++db)
       o[db][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, o[db][qb], 0, 0, 0);
     // row sums of the (rounded) weights on the matrix core: every row of ones . P^T
-    lacc[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf, lacc[qb], 0, 0, 0);
+    if constexpr (!PW) lacc[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf, lacc[qb], 0, 0, 0);
   };
   // One tile from LDS stage st for all four query blocks, with no branch between them.  Query
   // blocks past the segment's end hold zero queries and are never written; a wavefront whose
@@ -276,7 +287,7 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
 #pragma unroll
       for (int db = 0; db < DB; ++db) o[db][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    if (attempt == 1) {
+    if (!PW && attempt == 1) {
       // exact max of every query over its whole visible range: K only, straight from global
       float mx[kNQB];
 #pragma unroll
@@ -313,7 +324,7 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
     load(std::integral_constant<int, 0>{}, PFD);
     __syncthreads();
 
-    if (attempt == 0) {
+    if (!PW && attempt == 0) {
       // reference max = max of the first tile (tile 0 holds key 0, which every query sees)
       read_k(0);
 #pragma unroll
@@ -340,6 +351,7 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
       if constexpr (PFD > 3) { if (tile + 3 < tiles_wg) step(tail, std::integral_constant<int, 3>{}, tile + 3); }
     }
 
+    if constexpr (PW) break;                                     // no statistics, nothing to redo
     // A reference far below the true max shows up as an overflowed (or NaN) denominator of a
     // real query; then every wavefront of the block goes round again.
     bool bad = false;
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
   for (int qb = 0; qb < kNQB; ++qb) {
     const int qi = 16 * qb + r;
     if (qi < nq) {
-      const float inv = 1.0f / lacc[qb][0];
+      const float inv = PW ? inv_norm : 1.0f / lacc[qb][0];
       uint16_t* orow = out + ((int64_t)(tok0 + q0 + qi) * H + h) * D + 4 * gq;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
@@ -371,10 +383,10 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
   }
 }
 
-template <int D, int PFD, int WPS, int NQB>
+template <int D, int PFD, int WPS, int NQB, bool PW>
 hipError_t launch_one(const PoolGeom& g, const BatchDev& b, const uint16_t* q, uint16_t* out, float c,
-                      int64_t id_bytes, hipStream_t stream) {
-  auto kern = attn_prefill_kernel<D, PFD, WPS, NQB>;
+                      float inv_norm, int64_t id_bytes, hipStream_t stream) {
+  auto kern = attn_prefill_kernel<D, PFD, WPS, NQB, PW>;
   constexpr int kBlockQ = 64 * NQB;
   int q_blocks_max = (b.max_new + kBlockQ - 1) / kBlockQ;
   if (q_blocks_max < 1) q_blocks_max = 1;
@@ -389,7 +401,7 @@ hipError_t launch_one(const PoolGeom& g, const BatchDev& b, const uint16_t* q, u
   const int64_t grid = (int64_t)((n_pairs + kXcds - 1) / kXcds) * kXcds * q_blocks_max;
   if (grid <= 0 || grid > 0x7fffffffll) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), (size_t)id_bytes, stream, g, b, q, out, c,
-                     q_blocks_max, n_pairs, (int)(id_bytes / 4));
+                     inv_norm, q_blocks_max, n_pairs, (int)(id_bytes / 4));
   return hipGetLastError();
 }
 
@@ -402,10 +414,12 @@ bool attn_prefill_applicable(const PoolGeom& g, const BatchDev& b) {
 }
 
 hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
-                               float sm_scale, hipStream_t stream) {
+                               float sm_scale, float inv_norm, hipStream_t stream) {
   if (b.total_new <= 0 || b.batch <= 0) return hipSuccess;
   if (!attn_prefill_applicable(g, b)) return hipErrorInvalidValue;
-  const float c = sm_scale * 1.4426950408889634f;     // logits are exponentiated in base 2
+  const bool pw = inv_norm > 0.f;
+  // softmax logits are exponentiated in base 2; the pointwise scale stays in natural units
+  const float c = pw ? sm_scale : sm_scale * 1.4426950408889634f;
   // table entries one block may touch: its tiles end at most one tile past max_total_len
   const int64_t id_bytes = (((int64_t)b.max_total_len + g.S - 1) / g.S + 4) * 4;
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(q);
@@ -414,8 +428,12 @@ hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, cons
   // in order and leaves its LDS operand reads and MFMA -> VALU dependencies exposed.  At
   // D = 128 that means 32 queries per wavefront (64-register accumulator) and 128-query blocks.
   switch (g.D) {
-    case 64: return launch_one<64, 3, 2, 4>(g, b, qp, op, c, id_bytes, stream);
-    case 128: return launch_one<128, 2, 2, 2>(g, b, qp, op, c, id_bytes, stream);
+    case 64:
+      return pw ? launch_one<64, 3, 2, 4, true>(g, b, qp, op, c, inv_norm, id_bytes, stream)
+                : launch_one<64, 3, 2, 4, false>(g, b, qp, op, c, 0.f, id_bytes, stream);
+    case 128:
+      return pw ? launch_one<128, 2, 2, 2, true>(g, b, qp, op, c, inv_norm, id_bytes, stream)
+                : launch_one<128, 2, 2, 2, false>(g, b, qp, op, c, 0.f, id_bytes, stream);
     default: return hipErrorInvalidValue;
   }
 }

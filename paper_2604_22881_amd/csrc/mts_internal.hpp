@@ -50,12 +50,15 @@ struct AttnPlan {
 };
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b);
 
+// inv_norm selects the aggregation: 0 = softmax (Sec. 2, Eq. 6-7); > 0 = pointwise,
+// out = inv_norm * sum_j silu(sm_scale * q.k_j) v_j (no softmax statistics).
 hipError_t launch_attn_generic(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
-                               float sm_scale, hipStream_t stream);
+                               float sm_scale, float inv_norm, hipStream_t stream);
 bool attn_prefill_applicable(const PoolGeom& g, const BatchDev& b);
 hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
-                               float sm_scale, hipStream_t stream);
+                               float sm_scale, float inv_norm, hipStream_t stream);
 hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
-                            const BatchDev& b, float sm_scale, void* workspace, hipStream_t stream);
+                            const BatchDev& b, float sm_scale, float inv_norm, void* workspace,
+                            hipStream_t stream);
 
 }  // namespace mts

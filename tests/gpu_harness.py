@@ -68,6 +68,15 @@ class GpuStep:
         torch.cuda.synchronize()
         return to_host(out[:w.total_new], w.np_dtype)
 
+    def attention_pointwise(self, data, layer, inv_norm, sm_scale=0.0):
+        w = self.w
+        q = to_dev(data["q"][layer])
+        out = torch.full((max(w.total_new, 1), w.heads, w.head_dim), -1, dtype=q.dtype, device=DEV)
+        mts.mts_attn_pointwise(self.cache.desc, layer, q, out, self.batch.meta, inv_norm, sm_scale,
+                               self.ws, self.ws_bytes)
+        torch.cuda.synchronize()
+        return to_host(out[:w.total_new], w.np_dtype)
+
     def pack(self, layer, users, positions, counts):
         w = self.w
         segs = SegmentList(users, positions, counts, DEV)

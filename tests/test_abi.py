@@ -119,6 +119,10 @@ def test_bad_batches_and_buffers_are_rejected():
     assert _code(mts.mts_attn_incremental, d, 0, FAKE, FAKE, _meta(), sm_scale=-1.0, stream=0) == B.MTS_ERR_INVALID_ARG
     assert _code(mts.mts_attn_incremental, d, 0, FAKE, FAKE, _meta(), sm_scale=float("nan"), stream=0) == B.MTS_ERR_INVALID_ARG
     assert _code(mts.mts_attn_incremental, d, 0, FAKE, FAKE, _meta(page_indices=None), stream=0) == B.MTS_ERR_INVALID_ARG
+    for bad in (0.0, -0.5, float("nan"), float("inf")):
+        assert _code(mts.mts_attn_pointwise, d, 0, FAKE, FAKE, _meta(), bad, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(mts.mts_attn_pointwise, d, 0, None, FAKE, _meta(), 0.5, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(mts.mts_attn_pointwise, d, 0, FAKE, FAKE, _meta(), 0.5, sm_scale=-1.0, stream=0) == B.MTS_ERR_INVALID_ARG
 
 
 def test_missing_or_short_workspace_is_rejected():
