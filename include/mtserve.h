@@ -61,7 +61,8 @@ enum {
   MTS_ERR_UNSUPPORTED = -2, /* dtype / head_dim / page_size outside the supported set */
   MTS_ERR_SHAPE = -3,       /* sizes inconsistent with each other */
   MTS_ERR_WORKSPACE = -4,   /* workspace missing or too small */
-  MTS_ERR_HIP = -5          /* the HIP runtime refused a launch or a copy */
+  MTS_ERR_HIP = -5,         /* the HIP runtime refused a launch or a copy */
+  MTS_ERR_BUSY = -6         /* admission control refused the task (offload quota / buffer space); nothing was enqueued */
 };
 
 enum { MTS_F32 = 0, MTS_BF16 = 1 };
@@ -186,6 +187,79 @@ int32_t mts_attn_pointwise(const mts_cache_desc* cache, int32_t layer, const voi
  * copy to be asynchronous (Sec. 4.2, DMA between pinned buffers and the onload / offload buffers). */
 int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream);
 int32_t mts_stage_d2h_async(void* host_dst, const void* device_src, int64_t bytes, void* stream);
+
+/*
+ * ---- Transfer pipeline -------------------------------------------------------------------
+ * The two background paths either side of the kernels (Sec. 4.2 "Pipelined Onload via Double
+ * Buffering", "Transient Offload Pipeline", "Offload Capacity Control"; Sec. 4.4 four-stream
+ * model and layer-wise synchronisation; Alg. 1 steps 2, 7, 8.3, 9).  An mts_xfer owns, on the
+ * device that is current at creation: an onload stream, a scatter stream and an offload stream
+ * (default priority, non-blocking), two pinned host buffers per direction, a device arena for
+ * transient offload buffers, one host worker per direction and a pool of copy threads.  These
+ * are the only functions of the library that allocate, create threads or block the host.
+ *
+ * Onload of a step: for every layer, each run is copied from the caller's host chunk into a
+ * pinned buffer (host threads) while the other pinned buffer is in flight to the device
+ * (onload stream); when a layer's runs have landed in `staging`, mts_kv_unpack of that layer
+ * is enqueued on the scatter stream and an event is recorded.  mts_xfer_onload_wait_layer
+ * makes a compute stream wait for exactly that event, so layer l's attention starts as soon
+ * as layer l is scattered, while deeper layers are still on the bus.
+ *
+ * Offload of a step: after the work already enqueued on `after_stream` (the step's appends),
+ * every layer's runs are gathered by mts_kv_pack into a transient buffer from the arena
+ * (offload stream), copied to the pinned buffers in turn, and copied from there into the
+ * caller's host chunks by the copy threads while the next buffer is in flight.  A task is
+ * refused with MTS_ERR_BUSY, before anything is enqueued, if the tokens pending in transient
+ * buffers would exceed the quota or the arena has no room.
+ */
+typedef struct mts_xfer mts_xfer;
+
+typedef struct mts_xfer_config {
+  int64_t pinned_bytes;         /* bytes of each pinned buffer: the host chunk size, >= the largest run */
+  int64_t offload_arena_bytes;  /* device bytes for transient offload buffers (0: no offload path) */
+  int64_t offload_quota_tokens; /* most run tokens that may be pending in transient buffers */
+  int32_t num_layers;           /* layers a task covers (= cache->num_layers of every call) */
+  int32_t copy_threads;         /* host threads per bulk copy, >= 1 */
+} mts_xfer_config;
+
+/* The runs of one task; the first five fields are exactly the arguments of mts_kv_unpack /
+ * mts_kv_pack and stay valid until the task has finished. */
+typedef struct mts_xfer_runs {
+  int32_t        num_segs;
+  const int32_t* seg_user;        /* device [num_segs] */
+  const int32_t* seg_pos;         /* device [num_segs] */
+  const int64_t* seg_tok_indptr;  /* device [num_segs+1] */
+  int32_t        max_seg_tokens;
+  const int64_t* host_tok_indptr; /* host copy of seg_tok_indptr; read during submit only */
+  void* const*   host_runs;       /* host [num_layers * num_segs]: run s of layer l, contiguous layout
+                                     [2][n_s][H][D], ordinary (pageable) memory; read (onload) or
+                                     written (offload) until the task has finished; the array itself
+                                     is read during submit only */
+} mts_xfer_runs;
+
+int32_t mts_xfer_create(const mts_xfer_config* config, mts_xfer** out);
+/* Waits for all submitted work, then frees everything.  NULL is a no-op. */
+int32_t mts_xfer_destroy(mts_xfer* x);
+
+/* Starts the onload of one step and returns at once.  `staging` is the device onload buffer:
+ * layer l's runs are laid out at staging + l * staging_layer_stride_bytes exactly as
+ * mts_kv_unpack expects them.  One onload task at a time: a second submit waits for the first
+ * to be fully enqueued.  cache and meta are copied; the arrays they point to must stay valid. */
+int32_t mts_xfer_onload_submit(mts_xfer* x, const mts_cache_desc* cache, const mts_batch_meta* meta,
+                               const mts_xfer_runs* runs, void* staging,
+                               int64_t staging_layer_stride_bytes);
+/* Blocks the calling host thread until layer `layer` of the current onload task has been
+ * enqueued (bounded wait), then makes `compute_stream` wait for its scatter (Alg. 1 step 8.3). */
+int32_t mts_xfer_onload_wait_layer(mts_xfer* x, int32_t layer, void* compute_stream);
+
+/* Queues the offload of one step and returns at once, or refuses it (MTS_ERR_BUSY). */
+int32_t mts_xfer_offload_submit(mts_xfer* x, const mts_cache_desc* cache, const mts_batch_meta* meta,
+                                const mts_xfer_runs* runs, void* after_stream);
+/* Run tokens currently pending in transient buffers (the quantity the quota bounds). */
+int64_t mts_xfer_offload_pending_tokens(mts_xfer* x);
+/* Blocks until every submitted task of both directions has finished (host data in place,
+ * device work complete).  Returns the first error a background task met, if any. */
+int32_t mts_xfer_drain(mts_xfer* x);
 
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char* mts_last_error(void);

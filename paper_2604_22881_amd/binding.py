@@ -15,12 +15,15 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG_DIR, "libmtserve_hip.so")
 
 MTS_OK, MTS_ERR_INVALID_ARG, MTS_ERR_UNSUPPORTED, MTS_ERR_SHAPE, MTS_ERR_WORKSPACE, MTS_ERR_HIP = 0, -1, -2, -3, -4, -5
+MTS_ERR_BUSY = -6
 MTS_F32, MTS_BF16 = 0, 1
 
 EXPORTS = (
     "mts_page_bytes", "mts_pages_for", "mts_elem_offset", "mts_kv_unpack", "mts_kv_pack",
     "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_pointwise",
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
+    "mts_xfer_create", "mts_xfer_destroy", "mts_xfer_onload_submit", "mts_xfer_onload_wait_layer",
+    "mts_xfer_offload_submit", "mts_xfer_offload_pending_tokens", "mts_xfer_drain",
 )
 
 
@@ -40,6 +43,17 @@ class BatchMeta(C.Structure):
     _fields_ = [("batch", C.c_int32), ("page_indptr", C.c_void_p), ("page_indices", C.c_void_p),
                 ("prefix_lens", C.c_void_p), ("new_indptr", C.c_void_p), ("total_new", C.c_int32),
                 ("max_new", C.c_int32), ("max_total_len", C.c_int32), ("total_pages", C.c_int32)]
+
+
+class XferConfig(C.Structure):
+    _fields_ = [("pinned_bytes", C.c_int64), ("offload_arena_bytes", C.c_int64),
+                ("offload_quota_tokens", C.c_int64), ("num_layers", C.c_int32), ("copy_threads", C.c_int32)]
+
+
+class XferRuns(C.Structure):
+    _fields_ = [("num_segs", C.c_int32), ("seg_user", C.c_void_p), ("seg_pos", C.c_void_p),
+                ("seg_tok_indptr", C.c_void_p), ("max_seg_tokens", C.c_int32),
+                ("host_tok_indptr", C.c_void_p), ("host_runs", C.c_void_p)]
 
 
 _lib = None
@@ -69,6 +83,13 @@ def lib():
         "mts_attn_pointwise": (I32, [DESC, I32, P, P, META, F32, F32, P, I64, P]),
         "mts_stage_h2d_async": (I32, [P, P, I64, P]),
         "mts_stage_d2h_async": (I32, [P, P, I64, P]),
+        "mts_xfer_create": (I32, [C.POINTER(XferConfig), C.POINTER(P)]),
+        "mts_xfer_destroy": (I32, [P]),
+        "mts_xfer_onload_submit": (I32, [P, DESC, META, C.POINTER(XferRuns), P, I64]),
+        "mts_xfer_onload_wait_layer": (I32, [P, I32, P]),
+        "mts_xfer_offload_submit": (I32, [P, DESC, META, C.POINTER(XferRuns), P]),
+        "mts_xfer_offload_pending_tokens": (I64, [P]),
+        "mts_xfer_drain": (I32, [P]),
         "mts_last_error": (C.c_char_p, []),
         "mts_version": (I32, []),
     }
@@ -162,6 +183,42 @@ def mts_attn_pointwise(desc, layer, q, out, meta, inv_norm, sm_scale=0.0, worksp
     return _check(lib().mts_attn_pointwise(C.byref(desc), layer, _ptr(q), _ptr(out), C.byref(meta),
                                            float(sm_scale), float(inv_norm), _ptr(workspace),
                                            int(workspace_bytes), _stream(stream)))
+
+
+# ---- transfer pipeline --------------------------------------------------------------------
+def mts_xfer_create(pinned_bytes, num_layers, offload_arena_bytes=0, offload_quota_tokens=0, copy_threads=4):
+    """Returns the opaque handle (an int)."""
+    cfg = XferConfig(int(pinned_bytes), int(offload_arena_bytes), int(offload_quota_tokens), int(num_layers),
+                     int(copy_threads))
+    handle = C.c_void_p()
+    _check(lib().mts_xfer_create(C.byref(cfg), C.byref(handle)))
+    return handle.value
+
+
+def mts_xfer_destroy(handle):
+    return _check(lib().mts_xfer_destroy(handle))
+
+
+def mts_xfer_onload_submit(handle, desc, meta, runs: XferRuns, staging, staging_layer_stride_bytes):
+    return _check(lib().mts_xfer_onload_submit(handle, C.byref(desc), C.byref(meta), C.byref(runs), _ptr(staging),
+                                               int(staging_layer_stride_bytes)))
+
+
+def mts_xfer_onload_wait_layer(handle, layer, stream=None):
+    return _check(lib().mts_xfer_onload_wait_layer(handle, int(layer), _stream(stream)))
+
+
+def mts_xfer_offload_submit(handle, desc, meta, runs: XferRuns, after_stream=None):
+    return _check(lib().mts_xfer_offload_submit(handle, C.byref(desc), C.byref(meta), C.byref(runs),
+                                                _stream(after_stream)))
+
+
+def mts_xfer_offload_pending_tokens(handle):
+    return _check(lib().mts_xfer_offload_pending_tokens(handle))
+
+
+def mts_xfer_drain(handle):
+    return _check(lib().mts_xfer_drain(handle))
 
 
 def mts_stage_h2d_async(device_dst, host_src, nbytes, stream=None):

@@ -119,6 +119,14 @@ int64_t roundup(int64_t v, int m) { return (v + m - 1) / m * m; }
 
 namespace mts {
 
+int32_t set_error(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   AttnPlan p{};
   p.use_mfma = (g.es == 2);

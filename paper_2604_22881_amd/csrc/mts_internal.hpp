@@ -8,6 +8,9 @@
 
 namespace mts {
 
+// records the calling thread's error text (what mts_last_error returns) and returns `code`
+int32_t set_error(int32_t code, const char* fmt, ...);
+
 struct BatchDev {            // device metadata arrays, as in mts_batch_meta
   int32_t        batch;
   const int32_t* page_indptr;

@@ -92,3 +92,27 @@ class SegmentList:
 
     def args(self):
         return (self.num_segs, self.seg_user, self.seg_pos, self.seg_tok_indptr, self.max_seg_tokens)
+
+
+class HostRuns:
+    """The host side of a transfer task: for every (layer, run) a contiguous numpy array in the
+    [2][n][H][D] layout (ordinary pageable memory, standing in for host chunks), and the
+    mts_xfer_runs structure that points at them.  Keeps everything it points to alive."""
+
+    def __init__(self, segs: SegmentList, arrays):
+        """arrays[layer][run] : C-contiguous numpy arrays."""
+        import ctypes as C
+        self.segs = segs
+        self.arrays = arrays
+        layers = len(arrays)
+        ptrs = (C.c_void_p * max(1, layers * segs.num_segs))()
+        for l in range(layers):
+            assert len(arrays[l]) == segs.num_segs
+            for s, a in enumerate(arrays[l]):
+                assert a.flags["C_CONTIGUOUS"]
+                ptrs[l * segs.num_segs + s] = a.ctypes.data
+        self._ptrs = ptrs
+        self._indptr = np.ascontiguousarray(segs.host_indptr, dtype=np.int64)
+        self.runs = B.XferRuns(segs.num_segs, segs.seg_user.data_ptr(), segs.seg_pos.data_ptr(),
+                               segs.seg_tok_indptr.data_ptr(), segs.max_seg_tokens,
+                               self._indptr.ctypes.data, C.addressof(ptrs))

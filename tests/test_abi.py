@@ -157,3 +157,27 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_transfer_pipeline_rejects_bad_arguments():
+    """Host-side validation of the mts_xfer_* calls; creating a pipeline needs a GPU, so without
+    one the call must come back with an error code, not crash."""
+    for kw in (dict(pinned_bytes=0, num_layers=2), dict(pinned_bytes=1 << 20, num_layers=0),
+               dict(pinned_bytes=1 << 20, num_layers=2, copy_threads=0),
+               dict(pinned_bytes=1 << 20, num_layers=2, offload_arena_bytes=-1)):
+        with pytest.raises(mts.MtsError) as e:
+            mts.mts_xfer_create(**kw)
+        assert e.value.code == B.MTS_ERR_INVALID_ARG
+    lib = B.lib()
+    assert lib.mts_xfer_destroy(None) == B.MTS_OK
+    assert lib.mts_xfer_drain(None) == B.MTS_ERR_INVALID_ARG
+    assert lib.mts_xfer_onload_wait_layer(None, 0, None) == B.MTS_ERR_INVALID_ARG
+    assert lib.mts_xfer_offload_pending_tokens(None) == B.MTS_ERR_INVALID_ARG
+    runs = B.XferRuns(0, None, None, None, 0, None, None)
+    assert lib.mts_xfer_onload_submit(None, C.byref(_desc()), C.byref(_meta()), C.byref(runs), None, 0) == B.MTS_ERR_INVALID_ARG
+    try:
+        h = mts.mts_xfer_create(pinned_bytes=1 << 16, num_layers=2)
+    except mts.MtsError as err:
+        assert err.code == B.MTS_ERR_HIP          # no device here
+    else:
+        mts.mts_xfer_destroy(h)
