@@ -33,6 +33,10 @@ def parse():
     ap.add_argument("--workload", default="batched_incremental")
     ap.add_argument("--attention", choices=("softmax", "pointwise"), default="softmax",
                     help="aggregation: mts_attn_incremental (default) or mts_attn_pointwise")
+    ap.add_argument("--host-transfer", action="store_true",
+                    help="also time the step with restored users' histories in ordinary host memory, moved by "
+                         "the transfer pipeline (mts_xfer_*), and the pipeline's host-to-device rate; adds a "
+                         "\"transfer\" object to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
     ap.add_argument("--no-miss", action="store_true", help="diagnostic: no restored users (no unpack, no per-layer wait)")
@@ -97,6 +101,90 @@ def cpu_baseline(w, budget_s=12.0, pointwise=False):
             "sample": f"{passes} (user, layer) passes over the workload's users in order, whole histories, all "
                       f"heads: unpack + append + attention in fp64, {t_used:.1f} s of CPU work; rate divided by "
                       f"the {w.layers} layers of a step"}
+
+
+def host_transfer_leg(args, w, cache, batch, miss_segs, evict_segs, q, k_new, v_new, out, ws, ws_bytes, compute,
+                      pointwise, inv_norm):
+    """The same step with the restored users' histories in ordinary (pageable) host memory: the
+    transfer pipeline copies each run into a pinned buffer, sends it to the onload buffer and
+    scatters layer by layer, the compute stream waits per layer (Sec. 4.2, 4.4); packed users go
+    back to host memory through the offload path.  Eager launches (the per-layer wait blocks the
+    host until the scatter is enqueued).  Also: the pipeline's host-to-device rate on its own,
+    beside one plain hipMemcpyAsync of the same bytes from pinned memory."""
+    import numpy as np
+    import torch
+    import paper_2604_22881_amd as mts
+    from paper_2604_22881_amd.runtime import HostRuns
+    L, H, D = w.layers, w.heads, w.head_dim
+    row = 2 * H * D * 2
+    rng = np.random.default_rng(w.seed)
+    cnt = np.diff(miss_segs.host_indptr)
+    on_arrays = [[rng.integers(0, 1 << 14, size=(2, int(n), H, D), dtype=np.uint16) for n in cnt] for _ in range(L)]
+    on_host = HostRuns(miss_segs, on_arrays)
+    stride = miss_segs.total_tokens * row
+    staging = torch.empty(L * stride, dtype=torch.uint8, device=cache.device)
+    ecnt = np.diff(evict_segs.host_indptr)
+    off_arrays = [[np.zeros((2, int(n), H, D), np.uint16) for n in ecnt] for _ in range(L)]
+    off_host = HostRuns(evict_segs, off_arrays)
+    etok = int(ecnt.sum())
+    xfer = mts.mts_xfer_create(pinned_bytes=w.chunk_tokens * row, num_layers=L,
+                               offload_arena_bytes=4 * (L * etok * row + 4096), offload_quota_tokens=4 * max(etok, 1),
+                               copy_threads=8)
+    refused = 0
+    try:
+        def step():
+            nonlocal refused
+            mts.mts_xfer_onload_submit(xfer, cache.desc, batch.meta, on_host.runs, staging, stride)
+            for l in range(L):
+                mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=compute)
+                mts.mts_xfer_onload_wait_layer(xfer, l, compute)
+                if pointwise:
+                    mts.mts_attn_pointwise(cache.desc, l, q[l], out[l], batch.meta, inv_norm, 0.0, ws, ws_bytes,
+                                           stream=compute)
+                else:
+                    mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=compute)
+            if etok:
+                try:
+                    mts.mts_xfer_offload_submit(xfer, cache.desc, batch.meta, off_host.runs, compute)
+                except mts.MtsError as e:
+                    if e.code != mts.MTS_ERR_BUSY:
+                        raise
+                    refused += 1
+        K = max(10, args.steps // 4)
+        for _ in range(3):
+            step()
+        mts.mts_xfer_drain(xfer); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            step()
+        compute.synchronize()                      # the step is over when its attention is; offload is background
+        t1 = time.perf_counter()
+        mts.mts_xfer_drain(xfer); torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        # the onload path alone
+        reps = 5
+        t3 = time.perf_counter()
+        for _ in range(reps):
+            mts.mts_xfer_onload_submit(xfer, cache.desc, batch.meta, on_host.runs, staging, stride)
+            mts.mts_xfer_drain(xfer)
+        t4 = time.perf_counter()
+    finally:
+        mts.mts_xfer_destroy(xfer)
+    h2d_bytes = L * stride
+    pinned = torch.empty(h2d_bytes, dtype=torch.uint8, pin_memory=True)
+    torch.cuda.synchronize()
+    t5 = time.perf_counter()
+    for _ in range(reps):
+        mts.mts_stage_h2d_async(staging, pinned, h2d_bytes, stream=compute)
+    compute.synchronize()
+    t6 = time.perf_counter()
+    return {"ms_per_step": (t1 - t0) * 1e3 / K, "steps": K, "launch": "eager",
+            "h2d_bytes_per_step": h2d_bytes, "d2h_bytes_per_step": L * etok * row,
+            "offload_tasks_refused": refused, "offload_drain_ms_after_last_step": (t2 - t1) * 1e3,
+            "onload_alone_gbps": h2d_bytes * reps / (t4 - t3) / 1e9,
+            "plain_pinned_h2d_gbps": h2d_bytes * reps / (t6 - t5) / 1e9,
+            "note": "pageable host runs -> pinned ping-pong -> onload buffer -> per-layer scatter; "
+                    "PCIe-inclusive, never the headline value"}
 
 
 def main():
@@ -258,6 +346,9 @@ def main():
     if os.path.exists(traffic_file) and not pointwise:          # measured HBM bytes per launch, from rocprofv3 --pmc runs
         with open(traffic_file) as f:
             res["roofline"]["traffic"] = json.load(f).get("hbm_bytes_per_launch")
+    if args.host_transfer and miss_segs.num_segs:
+        res["transfer"] = host_transfer_leg(args, w, cache, batch, miss_segs, evict_segs, q, k_new, v_new, out, ws,
+                                            ws_bytes, compute, pointwise, inv_norm)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, pointwise=pointwise)
     print(json.dumps(res))
