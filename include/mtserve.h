@@ -261,6 +261,70 @@ int64_t mts_xfer_offload_pending_tokens(mts_xfer* x);
  * device work complete).  Returns the first error a background task met, if any. */
 int32_t mts_xfer_drain(mts_xfer* x);
 
+/*
+ * ---- Cache manager (host only) -------------------------------------------------------------
+ * The KVCacheManager of Sec. 3.1 / Sec. 4.3: per-user sequence lengths, the page table of the
+ * GPU tier, page allocation from a free pool, LRU replacement with O(1) updates, eviction as a
+ * pure metadata operation (the host tier is the backup; nothing is copied), and the registry
+ * of locked users that victim selection skips.  It makes no device call: its output is the
+ * host copy of the arrays mts_batch_meta points to.  Not thread-safe: one caller at a time.
+ *
+ * Per user the manager tracks total_len (tokens of history cached on either tier), host_len
+ * (the prefix of those persisted in the host tier) and whether the GPU tier holds the user.
+ * Evicting a user frees its pages and cuts total_len back to host_len: tokens the offload
+ * path had not persisted yet are simply no longer cached (counted in tokens_dropped).
+ */
+typedef struct mts_cm mts_cm;
+
+typedef struct mts_cm_stats {
+  int64_t gpu_hits;       /* requests whose history was in the GPU tier */
+  int64_t host_hits;      /* requests whose history had to come up from the host tier */
+  int64_t cold_requests;  /* requests with no cached history at all */
+  int64_t evictions;      /* users evicted from the GPU tier */
+  int64_t tokens_dropped; /* tokens lost at eviction because they were not persisted yet */
+  int64_t free_pages;
+  int64_t users_tracked;
+  int64_t users_on_gpu;
+} mts_cm_stats;
+
+int32_t mts_cm_create(int32_t num_pages, int32_t page_size, int32_t host_chunk_tokens, mts_cm** out);
+int32_t mts_cm_destroy(mts_cm* m);
+
+/* Tokens of history cached for `user` on either tier; 0 for an unknown user (Alg. 1 step 1). */
+int32_t mts_cm_cached_length(mts_cm* m, int64_t user);
+
+/*
+ * Page allocation and LRU for one batch (Alg. 1 steps 2 and 6).  For request i (users[i]
+ * distinct, new_tokens[i] >= 0) the user is given ceil((total_len + new_tokens[i]) / page_size)
+ * pages: missing ones come from the free pool, and when that runs dry whole users are evicted
+ * from the least-recently-used end, skipping locked users and the users of this batch.
+ * Outputs (host arrays): prefix_lens[i] = total_len; onload_lens[i] = tokens that must be
+ * brought up from the host tier first (0 if the GPU tier holds the user; total_len otherwise);
+ * page_indptr[batch+1] / page_indices = the users' page lists in CSR form, logical order.
+ * MTS_ERR_BUSY: even after evicting every eligible victim the batch does not fit; MTS_ERR_SHAPE:
+ * page_capacity (entries of page_indices) is too small.  On any error nothing has changed.
+ */
+int32_t mts_cm_prepare_batch(mts_cm* m, const int64_t* users, const int32_t* new_tokens, int32_t batch,
+                             int32_t* prefix_lens, int32_t* onload_lens, int32_t* page_indptr,
+                             int32_t* page_indices, int64_t page_capacity);
+/* The prepared batch has run (Alg. 1 step 7): total_len += new_tokens, the users are on the
+ * GPU tier and become the most recently used, in batch order. */
+int32_t mts_cm_commit_batch(mts_cm* m);
+
+/* Offload trigger (Sec. 4.2): users on the GPU tier whose not-yet-persisted tokens amount to
+ * at least one host chunk.  Returns how many were written (<= capacity), most recent first:
+ * tokens [from_pos[k], from_pos[k] + count[k]) of users[k], count a multiple of the chunk.
+ * Each returned user is locked until mts_cm_offload_done. */
+int32_t mts_cm_offload_due(mts_cm* m, int64_t* users, int32_t* from_pos, int32_t* count, int32_t capacity);
+/* The host tier now holds tokens [0, persisted_len) of `user`; unlocks the user. */
+int32_t mts_cm_offload_done(mts_cm* m, int64_t user, int32_t persisted_len);
+/* Puts `user` into (locked != 0) or takes it out of the locked registry by hand. */
+int32_t mts_cm_set_locked(mts_cm* m, int64_t user, int32_t locked);
+
+/* Users evicted since the last call, in eviction order; returns how many were written. */
+int64_t mts_cm_take_evicted(mts_cm* m, int64_t* users, int64_t capacity);
+int32_t mts_cm_get_stats(mts_cm* m, mts_cm_stats* out);
+
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char* mts_last_error(void);
 

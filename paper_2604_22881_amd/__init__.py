@@ -6,5 +6,5 @@ from .binding import (  # noqa: F401
     mts_kv_unpack, mts_last_error, mts_page_bytes, mts_pages_for, mts_stage_d2h_async,
     mts_stage_h2d_async, mts_version, mts_xfer_create, mts_xfer_destroy, mts_xfer_drain,
     mts_xfer_offload_pending_tokens, mts_xfer_offload_submit, mts_xfer_onload_submit,
-    mts_xfer_onload_wait_layer, XferConfig, XferRuns, MTS_ERR_BUSY,
+    mts_xfer_onload_wait_layer, XferConfig, XferRuns, MTS_ERR_BUSY, CacheManager,
 )

@@ -24,6 +24,8 @@ EXPORTS = (
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
     "mts_xfer_create", "mts_xfer_destroy", "mts_xfer_onload_submit", "mts_xfer_onload_wait_layer",
     "mts_xfer_offload_submit", "mts_xfer_offload_pending_tokens", "mts_xfer_drain",
+    "mts_cm_create", "mts_cm_destroy", "mts_cm_cached_length", "mts_cm_prepare_batch", "mts_cm_commit_batch",
+    "mts_cm_offload_due", "mts_cm_offload_done", "mts_cm_set_locked", "mts_cm_take_evicted", "mts_cm_get_stats",
 )
 
 
@@ -54,6 +56,11 @@ class XferRuns(C.Structure):
     _fields_ = [("num_segs", C.c_int32), ("seg_user", C.c_void_p), ("seg_pos", C.c_void_p),
                 ("seg_tok_indptr", C.c_void_p), ("max_seg_tokens", C.c_int32),
                 ("host_tok_indptr", C.c_void_p), ("host_runs", C.c_void_p)]
+
+
+class CmStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("gpu_hits", "host_hits", "cold_requests", "evictions", "tokens_dropped",
+                                         "free_pages", "users_tracked", "users_on_gpu")]
 
 
 _lib = None
@@ -90,6 +97,16 @@ def lib():
         "mts_xfer_offload_submit": (I32, [P, DESC, META, C.POINTER(XferRuns), P]),
         "mts_xfer_offload_pending_tokens": (I64, [P]),
         "mts_xfer_drain": (I32, [P]),
+        "mts_cm_create": (I32, [I32, I32, I32, C.POINTER(P)]),
+        "mts_cm_destroy": (I32, [P]),
+        "mts_cm_cached_length": (I32, [P, I64]),
+        "mts_cm_prepare_batch": (I32, [P, P, P, I32, P, P, P, P, I64]),
+        "mts_cm_commit_batch": (I32, [P]),
+        "mts_cm_offload_due": (I32, [P, P, P, P, I32]),
+        "mts_cm_offload_done": (I32, [P, I64, I32]),
+        "mts_cm_set_locked": (I32, [P, I64, I32]),
+        "mts_cm_take_evicted": (I64, [P, P, I64]),
+        "mts_cm_get_stats": (I32, [P, C.POINTER(CmStats)]),
         "mts_last_error": (C.c_char_p, []),
         "mts_version": (I32, []),
     }
@@ -219,6 +236,65 @@ def mts_xfer_offload_pending_tokens(handle):
 
 def mts_xfer_drain(handle):
     return _check(lib().mts_xfer_drain(handle))
+
+
+# ---- cache manager (host only) ----------------------------------------------------------------
+class CacheManager:
+    """Thin holder of an mts_cm handle: numpy arrays in, numpy arrays out; every decision is
+    taken by the library."""
+
+    def __init__(self, num_pages, page_size, host_chunk_tokens=1024):
+        h = C.c_void_p()
+        _check(lib().mts_cm_create(int(num_pages), int(page_size), int(host_chunk_tokens), C.byref(h)))
+        self._h = h.value
+        self.num_pages, self.page_size = int(num_pages), int(page_size)
+
+    def close(self):
+        if self._h:
+            lib().mts_cm_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def cached_length(self, user):
+        return _check(lib().mts_cm_cached_length(self._h, int(user)))
+
+    def prepare_batch(self, users, new_tokens):
+        """-> (prefix_lens, onload_lens, page_indptr, page_indices), host int32 arrays."""
+        users = np.ascontiguousarray(users, dtype=np.int64)
+        new_tokens = np.ascontiguousarray(new_tokens, dtype=np.int32)
+        B = len(users)
+        prefix = np.zeros(max(B, 1), np.int32); onload = np.zeros(max(B, 1), np.int32)
+        indptr = np.zeros(B + 1, np.int32)
+        cap = self.num_pages
+        indices = np.zeros(max(cap, 1), np.int32)
+        _check(lib().mts_cm_prepare_batch(self._h, users.ctypes.data, new_tokens.ctypes.data, B, prefix.ctypes.data,
+                                          onload.ctypes.data, indptr.ctypes.data, indices.ctypes.data, cap))
+        return prefix[:B], onload[:B], indptr, indices[:indptr[B]].copy()
+
+    def commit_batch(self):
+        return _check(lib().mts_cm_commit_batch(self._h))
+
+    def offload_due(self, capacity=1024):
+        u = np.zeros(capacity, np.int64); p = np.zeros(capacity, np.int32); c = np.zeros(capacity, np.int32)
+        n = _check(lib().mts_cm_offload_due(self._h, u.ctypes.data, p.ctypes.data, c.ctypes.data, capacity))
+        return u[:n].copy(), p[:n].copy(), c[:n].copy()
+
+    def offload_done(self, user, persisted_len):
+        return _check(lib().mts_cm_offload_done(self._h, int(user), int(persisted_len)))
+
+    def set_locked(self, user, locked):
+        return _check(lib().mts_cm_set_locked(self._h, int(user), int(bool(locked))))
+
+    def take_evicted(self, capacity=1 << 16):
+        u = np.zeros(capacity, np.int64)
+        n = _check(lib().mts_cm_take_evicted(self._h, u.ctypes.data, capacity))
+        return u[:n].copy()
+
+    def stats(self):
+        st = CmStats()
+        _check(lib().mts_cm_get_stats(self._h, C.byref(st)))
+        return {n: int(getattr(st, n)) for n, _ in CmStats._fields_}
 
 
 def mts_stage_h2d_async(device_dst, host_src, nbytes, stream=None):
