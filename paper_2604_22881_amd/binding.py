@@ -244,6 +244,7 @@ class CacheManager:
     taken by the library."""
 
     def __init__(self, num_pages, page_size, host_chunk_tokens=1024):
+        self._h = None
         h = C.c_void_p()
         _check(lib().mts_cm_create(int(num_pages), int(page_size), int(host_chunk_tokens), C.byref(h)))
         self._h = h.value
