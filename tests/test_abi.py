@@ -181,3 +181,14 @@ def test_transfer_pipeline_rejects_bad_arguments():
         assert err.code == B.MTS_ERR_HIP          # no device here
     else:
         mts.mts_xfer_destroy(h)
+
+
+def test_shapes_beyond_the_schedule_are_refused_not_launched():
+    d = _desc()
+    too_many_users = _meta(batch=4097, total_new=4097, max_new=1, max_total_len=10, total_pages=4097)
+    with pytest.raises(mts.MtsError) as e:
+        mts.mts_attn_workspace_bytes(d, too_many_users)
+    assert e.value.code == B.MTS_ERR_UNSUPPORTED
+    assert _code(mts.mts_attn_incremental, d, 0, FAKE, FAKE, too_many_users, workspace=FAKE, workspace_bytes=1 << 30,
+                 stream=0) == B.MTS_ERR_UNSUPPORTED
+    assert _code(mts.mts_kv_append, d, 0, FAKE, FAKE, _meta(batch=70000), stream=0) == B.MTS_ERR_INVALID_ARG

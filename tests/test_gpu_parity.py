@@ -274,3 +274,23 @@ def test_late_dominant_key_redoes_the_segment_with_the_exact_max(prefill, monkey
     check_attention(w, got, ref)
     # sanity of the construction: the dominant key really takes all the weight
     assert np.allclose(ref[lo:hi, 0], as_values(data["hist"][0][0][1, 555, 0]), atol=1e-6)
+
+
+EDGE_CASES = {
+    # the largest batch the schedule takes (its metadata fills ~64 KiB of LDS), tiny users
+    "batch_4096": lambda rng: ("bf16", 1, 1, 64, 16, rng.integers(0, 40, 4096), rng.integers(0, 4, 4096)),
+    # many heads, smallest head_dim
+    "heads_40_d32": lambda rng: ("bf16", 1, 40, 32, 16, [130, 0, 17], [9, 33, 1]),
+    # one very long history, few new tokens: hundreds of wavefronts share one (user, head)
+    "one_long_user": lambda rng: ("bf16", 1, 2, 128, 16, [70001], [5]),
+    # every new segment is a single token (decode shape) over page-aligned and unaligned prefixes
+    "decode_like": lambda rng: ("bf16", 1, 4, 64, 32, [0, 1, 31, 32, 33, 1024, 1025], [1] * 7),
+}
+
+
+@pytest.mark.parametrize("name", list(EDGE_CASES))
+def test_attention_edge_shapes(name):
+    rng = np.random.default_rng(len(name))
+    dtype, L, H, D, S, prefix, new = EDGE_CASES[name](rng)
+    w = W.custom_workload(name, 300 + len(name), dtype, L, H, D, S, np.asarray(prefix), np.asarray(new))
+    _attention_matches_oracle(w)
