@@ -6,8 +6,8 @@
 A step is one pass of the whole hot path over one batch of the synthetic workload: per layer
 mts_kv_append then mts_attn_incremental on the compute stream, while a side stream restores
 the batch's cache-miss users from an HBM-resident staging buffer (mts_kv_unpack, one event per
-layer that the layer's attention waits for, as in Alg. 1 step 8.3) and packs the users chosen
-for offload (mts_kv_pack).  All inputs are resident in HBM before the timed region.
+layer that the layer's attention waits for, as in Alg. 1 step 8.3) and, after the layer loop,
+packs the users chosen for offload (mts_kv_pack, Alg. 1 step 9).  All inputs are resident in HBM before the timed region.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -39,6 +39,9 @@ def parse():
                          "\"transfer\" object to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
+    ap.add_argument("--pack-per-layer", action="store_true",
+                    help="diagnostic: gather layer l's evicted runs right after layer l's append, concurrently "
+                         "with its attention, instead of after the layer loop")
     ap.add_argument("--no-miss", action="store_true", help="diagnostic: no restored users (no unpack, no per-layer wait)")
     ap.add_argument("--no-evict", action="store_true", help="diagnostic: no packed users")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -259,8 +262,13 @@ def main():
                 mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=cs)
             if attn_events is not None:
                 b.record(compute)
-            if evict_segs.num_segs:
+            if evict_segs.num_segs and args.pack_per_layer:
                 side.wait_event(ev_appended[l])
+                mts.mts_kv_pack(cache.desc, l, offload, *evict_segs.args(), batch.meta, stream=ss)
+        if evict_segs.num_segs and not args.pack_per_layer:
+            # Alg. 1 step 9: the offload is submitted after the layer loop, behind the last append
+            side.wait_event(ev_appended[L - 1])
+            for l in range(L):
                 mts.mts_kv_pack(cache.desc, l, offload, *evict_segs.args(), batch.meta, stream=ss)
 
     for _ in range(args.warmup):
