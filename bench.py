@@ -194,7 +194,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
-              "(the path shards by user with no exchange step; see DESIGN.md)", file=sys.stderr)
+              "(the path shards by user, with no exchange step between GPUs)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

@@ -1,4 +1,4 @@
-"""GPU parity at BASELINE's full sizes, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of the benchmark workloads, in the launch configuration bench.py times.
 
 The oracle cannot redo 10^5 .. 3x10^5 tokens x all heads in seconds, so each workload is
 checked (a) element by element on sampled (user, head) pairs whose K/V/Q are seeded host data

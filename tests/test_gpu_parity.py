@@ -188,7 +188,7 @@ def test_long_new_segments_through_the_streaming_kernel(name, monkeypatch):
 
 
 def test_tiny_reuse_config_matches_oracle_and_recompute():
-    """BASELINE config 1 (1 user, L2 H4 D32 fp32, prefix 256 + 16 new, block 16)."""
+    """The tiny reuse-versus-recompute configuration (1 user, L2 H4 D32 fp32, prefix 256 + 16 new, block 16)."""
     G = _harness()
     w = W.make_workload("tiny_reuse")
     data = draw_step_data(w)

@@ -1,4 +1,4 @@
-"""Host-staging path (BASELINE config 4, reduced size): cache-miss users' contiguous host KV
+"""Host-staging path (the host_staging workload, reduced size): cache-miss users' contiguous host KV
 is copied with hipMemcpyAsync from pinned memory on a side stream and unpacked into pages,
 layer by layer, while the compute stream appends and attends; each layer's attention waits
 only for that layer's event (Alg. 1 step 8.3).  Evicted users are packed and copied back:

@@ -36,7 +36,7 @@ def _reuse_and_recompute(w, layer=0):
 
 
 def test_reuse_equals_recompute_tiny_config():
-    """BASELINE config 1: prefix 256 + 16 new tokens, fp32, block size 16."""
+    """The tiny reuse-versus-recompute configuration: prefix 256 + 16 new tokens, fp32, block size 16."""
     w = W.make_workload("tiny_reuse")
     assert _reuse_and_recompute(w, layer=1) < 1e-12
 
