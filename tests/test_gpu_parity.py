@@ -294,3 +294,23 @@ def test_attention_edge_shapes(name):
     dtype, L, H, D, S, prefix, new = EDGE_CASES[name](rng)
     w = W.custom_workload(name, 300 + len(name), dtype, L, H, D, S, np.asarray(prefix), np.asarray(new))
     _attention_matches_oracle(w)
+
+
+def _random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.integers(1, 7))
+    H, D, S = int(rng.integers(1, 6)), int(rng.choice([32, 64, 128])), int(rng.choice([16, 32, 64]))
+    long_new = seed % 4 == 0                       # every fourth case has prefill-sized new segments
+    prefix = rng.integers(0, 700, B) * (rng.random(B) > 0.2)
+    new = rng.integers(0, 600 if long_new else 70, B)
+    if new.sum() == 0:
+        new[0] = 1
+    return W.custom_workload(f"rand{seed}", 500 + seed, "bf16", 1, H, D, S, prefix.astype(np.int64), new.astype(np.int64),
+                             chunk_tokens=int(rng.choice([64, 256, 1024])))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_attention_random_shapes(seed):
+    """Seeded random shapes (users, heads, head_dim, page size, ragged prefixes and new segments,
+    empty users): whichever kernel the library picks must agree with the oracle."""
+    _attention_matches_oracle(_random_case(seed))
