@@ -314,3 +314,39 @@ def test_attention_random_shapes(seed):
     """Seeded random shapes (users, heads, head_dim, page size, ragged prefixes and new segments,
     empty users): whichever kernel the library picks must agree with the oracle."""
     _attention_matches_oracle(_random_case(seed))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_data_movement_random_shapes(seed):
+    """Long and short runs at unaligned positions, both element types, every head_dim / page size:
+    the pool image after unpack and append, and packs of random sub-ranges, bit for bit."""
+    G = _harness()
+    rng = np.random.default_rng(2000 + seed)
+    dtype = "f32" if seed % 3 == 0 else "bf16"
+    H, D, S = int(rng.integers(1, 4)), int(rng.choice([32, 64, 128])), int(rng.choice([16, 32, 64]))
+    B = int(rng.integers(1, 5))
+    prefix = rng.integers(0, 900, B)
+    new = rng.integers(0, 400, B)
+    w = W.custom_workload(f"mv{seed}", 700 + seed, dtype, 1, H, D, S, prefix.astype(np.int64), new.astype(np.int64),
+                          chunk_tokens=int(rng.choice([100, 129, 256, 1000])))
+    data = draw_step_data(w)
+    step = G.GpuStep(w, fill_byte=FILL)
+    step.unpack_histories(data, 0)
+    store = _oracle_store(w, data, do_append=False)
+    assert np.array_equal(step.pool_image(0), G.expected_pool_image(w, store, 0, FILL)), "after unpack"
+    step.append(data, 0)
+    store = _oracle_store(w, data, do_append=True)
+    assert np.array_equal(step.pool_image(0), G.expected_pool_image(w, store, 0, FILL)), "after append"
+    users, pos, cnt = [], [], []
+    for u in range(w.batch):
+        T = int(w.total_lens[u])
+        for _ in range(3):
+            if T == 0:
+                continue
+            a = int(rng.integers(0, T)); n = int(rng.integers(1, T - a + 1))
+            users.append(u); pos.append(a); cnt.append(n)
+    if users:
+        got = step.pack(0, users, pos, cnt)
+        for u, p, n, g in zip(users, pos, cnt, got):
+            assert g.tobytes() == oracle.pack(store, 0, w.user_pages(u), p, n).tobytes(), f"pack user {u} [{p},{p+n})"
+    assert np.array_equal(step.pool_image(0), G.expected_pool_image(w, store, 0, FILL)), "pack must not write the pool"
