@@ -21,6 +21,9 @@
  *   - Arguments are validated on the host before anything is launched; a call that returns
  *     an error has launched nothing.  mts_last_error() describes the last error of the
  *     calling thread.
+ *   - The kernel entry points may be called from several host threads and may be captured into
+ *     a HIP graph.  The first attention call of a process queries the device (occupancy, LDS
+ *     limits): make one call outside stream capture before capturing.
  *   - Device-resident metadata (page ids, lengths) cannot be validated on the host.  The
  *     kernels skip any access whose page id is outside [0, num_pages) or whose token lies
  *     beyond the user's page list, so bad metadata gives wrong results, not a fault.
