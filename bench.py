@@ -130,9 +130,9 @@ def host_transfer_leg(args, w, cache, batch, miss_segs, evict_segs, q, k_new, v_
     off_arrays = [[np.zeros((2, int(n), H, D), np.uint16) for n in ecnt] for _ in range(L)]
     off_host = HostRuns(evict_segs, off_arrays)
     etok = int(ecnt.sum())
-    xfer = mts.mts_xfer_create(pinned_bytes=w.chunk_tokens * row, num_layers=L,
+    xfer = mts.mts_xfer_create(pinned_bytes=8 * w.chunk_tokens * row, num_layers=L,
                                offload_arena_bytes=4 * (L * etok * row + 4096), offload_quota_tokens=4 * max(etok, 1),
-                               copy_threads=8)
+                               copy_threads=6)
     refused = 0
     try:
         def step():

@@ -218,11 +218,13 @@ int32_t mts_stage_d2h_async(void* host_dst, const void* device_src, int64_t byte
 typedef struct mts_xfer mts_xfer;
 
 typedef struct mts_xfer_config {
-  int64_t pinned_bytes;         /* bytes of each pinned buffer: the host chunk size, >= the largest run */
+  int64_t pinned_bytes;         /* bytes of each pinned buffer: >= the largest run (one host chunk); a
+                                   multiple of it lets several consecutive runs share one DMA */
   int64_t offload_arena_bytes;  /* device bytes for transient offload buffers (0: no offload path) */
   int64_t offload_quota_tokens; /* most run tokens that may be pending in transient buffers */
   int32_t num_layers;           /* layers a task covers (= cache->num_layers of every call) */
-  int32_t copy_threads;         /* host threads per bulk copy, >= 1 */
+  int32_t copy_threads;         /* host threads per bulk copy and direction, >= 1; they poll between the
+                                   copies of a task, so keep 2 * copy_threads below the core count */
 } mts_xfer_config;
 
 /* The runs of one task; the first five fields are exactly the arguments of mts_kv_unpack /

@@ -33,7 +33,10 @@ namespace {
 
 constexpr auto kHostWait = std::chrono::seconds(60);   // every host-side wait is bounded by this
 
-// n-way memcpy: the calling thread takes the first slice, n-1 helpers the others.
+// n-way memcpy: the calling thread takes the first slice, n-1 helpers the others.  A run is a
+// couple of megabytes, i.e. tens of microseconds per slice, so waking helpers through a
+// condition variable would cost as much as the copy: between the copies of one task the helpers
+// poll a generation counter (for at most kSpin), and only then go to sleep.
 class CopyPool {
  public:
   explicit CopyPool(int n) : n_(n < 1 ? 1 : n) {
@@ -42,35 +45,39 @@ class CopyPool {
   ~CopyPool() {
     {
       std::lock_guard<std::mutex> g(mu_);
-      stop_ = true;
+      stop_.store(true);
     }
     cv_.notify_all();
     for (auto& t : helpers_) t.join();
   }
   void copy(void* dst, const void* src, size_t bytes) {
-    const size_t min_slice = 256 * 1024;
+    const size_t min_slice = 128 * 1024;
     int parts = (int)((bytes + min_slice - 1) / min_slice);
     if (parts > n_) parts = n_;
     if (parts <= 1) {
       memcpy(dst, src, bytes);
       return;
     }
+    dst_ = static_cast<char*>(dst);
+    src_ = static_cast<const char*>(src);
+    bytes_ = bytes;
+    parts_ = parts;
+    left_.store(n_ - 1, std::memory_order_relaxed);   // every helper acknowledges every generation
     {
-      std::lock_guard<std::mutex> g(mu_);
-      dst_ = static_cast<char*>(dst);
-      src_ = static_cast<const char*>(src);
-      bytes_ = bytes;
-      parts_ = parts;
-      left_ = parts - 1;
-      ++gen_;
+      std::lock_guard<std::mutex> g(mu_);          // pairs with the helpers' sleep: no lost wake-up
+      gen_.fetch_add(1, std::memory_order_release);
     }
     cv_.notify_all();
     slice(0, parts, dst_, src_, bytes);
-    std::unique_lock<std::mutex> g(mu_);
-    done_.wait(g, [this] { return left_ == 0; });
+    while (left_.load(std::memory_order_acquire) != 0) cpu_relax();   // equal slices: a short wait
   }
 
  private:
+  static void cpu_relax() {
+#if defined(__x86_64__)
+    __builtin_ia32_pause();
+#endif
+  }
   static void slice(int i, int parts, char* dst, const char* src, size_t bytes) {
     const size_t per = (bytes / parts + 63) & ~(size_t)63;
     const size_t lo = (size_t)i * per;
@@ -81,34 +88,36 @@ class CopyPool {
   void loop(int i) {
     uint64_t seen = 0;
     for (;;) {
-      char* d;
-      const char* s;
-      size_t b;
-      int parts;
-      {
-        std::unique_lock<std::mutex> g(mu_);
-        cv_.wait(g, [&] { return stop_ || gen_ != seen; });
-        if (stop_) return;
-        seen = gen_;
-        d = dst_; s = src_; b = bytes_; parts = parts_;
+      // poll first, sleep if nothing comes
+      const auto t0 = std::chrono::steady_clock::now();
+      while (gen_.load(std::memory_order_acquire) == seen && !stop_.load(std::memory_order_relaxed)) {
+        cpu_relax();
+        if (std::chrono::steady_clock::now() - t0 > kSpin) {
+          std::unique_lock<std::mutex> g(mu_);
+          cv_.wait(g, [&] { return stop_.load() || gen_.load(std::memory_order_acquire) != seen; });
+          break;
+        }
       }
-      if (i < parts) {
-        slice(i, parts, d, s, b);
-        std::lock_guard<std::mutex> g(mu_);
-        if (--left_ == 0) done_.notify_all();
-      }
+      if (stop_.load()) return;
+      seen = gen_.load(std::memory_order_acquire);
+      // The fields below were written before gen_ was bumped and stay put until left_ reaches
+      // 0, which needs this helper's acknowledgement too: no helper is ever a generation behind.
+      if (i < parts_) slice(i, parts_, dst_, src_, bytes_);
+      left_.fetch_sub(1, std::memory_order_release);
     }
   }
+  static constexpr std::chrono::microseconds kSpin{50};
   const int n_;
   std::vector<std::thread> helpers_;
   std::mutex mu_;
-  std::condition_variable cv_, done_;
-  bool stop_ = false;
-  uint64_t gen_ = 0;
+  std::condition_variable cv_;
+  std::atomic<bool> stop_{false};
+  std::atomic<uint64_t> gen_{0};
+  std::atomic<int> left_{0};
   char* dst_ = nullptr;
   const char* src_ = nullptr;
   size_t bytes_ = 0;
-  int parts_ = 0, left_ = 0;
+  int parts_ = 0;
 };
 
 struct Task {
@@ -191,17 +200,30 @@ bool run_onload(mts_xfer* x, const Task& t, int32_t& err, char (&text)[256]) {
     XFER_HIP(hipStreamWaitEvent(x->s_onload, x->ev_layer_ready[L - 1], 0), err, text);
   int k = 0;
   for (int l = 0; l < L; ++l) {
-    for (int s = 0; s < t.num_segs; ++s) {
-      const int64_t bytes = (t.tok[s + 1] - t.tok[s]) * t.row_bytes;
-      if (bytes == 0) continue;
-      const int b = k & 1;
-      if (x->on_dma_used[b]) XFER_HIP(hipEventSynchronize(x->ev_on_dma[b]), err, text);   // pinned[b] has left for the device
-      x->pool_on->copy(x->pin_on[b], t.host[(size_t)l * t.num_segs + s], (size_t)bytes);
-      XFER_HIP(hipMemcpyAsync(t.staging + l * t.stride + t.tok[s] * t.row_bytes, x->pin_on[b], (size_t)bytes,
-                              hipMemcpyHostToDevice, x->s_onload), err, text);
-      XFER_HIP(hipEventRecord(x->ev_on_dma[b], x->s_onload), err, text);
-      x->on_dma_used[b] = true;
-      ++k;
+    // Consecutive runs of a layer are consecutive in the onload buffer: as many as fit one pinned
+    // buffer travel in one DMA (a copy of a megabyte or two is dominated by its fixed cost).
+    for (int s = 0; s < t.num_segs;) {
+      int e = s;
+      int64_t bytes = 0;
+      while (e < t.num_segs && (e == s || bytes + (t.tok[e + 1] - t.tok[e]) * t.row_bytes <= x->cfg.pinned_bytes)) {
+        bytes += (t.tok[e + 1] - t.tok[e]) * t.row_bytes;
+        ++e;
+      }
+      if (bytes > 0) {
+        const int b = k & 1;
+        if (x->on_dma_used[b]) XFER_HIP(hipEventSynchronize(x->ev_on_dma[b]), err, text);   // pinned[b] has left for the device
+        char* pin = static_cast<char*>(x->pin_on[b]);
+        for (int r = s; r < e; ++r) {
+          const int64_t rb = (t.tok[r + 1] - t.tok[r]) * t.row_bytes;
+          if (rb > 0) x->pool_on->copy(pin + (t.tok[r] - t.tok[s]) * t.row_bytes, t.host[(size_t)l * t.num_segs + r], (size_t)rb);
+        }
+        XFER_HIP(hipMemcpyAsync(t.staging + l * t.stride + t.tok[s] * t.row_bytes, pin, (size_t)bytes,
+                                hipMemcpyHostToDevice, x->s_onload), err, text);
+        XFER_HIP(hipEventRecord(x->ev_on_dma[b], x->s_onload), err, text);
+        x->on_dma_used[b] = true;
+        ++k;
+      }
+      s = e;
     }
     XFER_HIP(hipEventRecord(x->ev_layer_dma[l], x->s_onload), err, text);
     XFER_HIP(hipStreamWaitEvent(x->s_scatter, x->ev_layer_dma[l], 0), err, text);
@@ -258,11 +280,14 @@ bool run_offload(mts_xfer* x, const Task& t, int32_t& err, char (&text)[256]) {
   char* region = x->arena + t.arena_off;
   int k = 0;
   bool have_prev = false;
-  void* prev_dst = nullptr;
-  int64_t prev_bytes = 0;
-  auto drain_prev = [&](int b) -> bool {   // pinned[b] -> host chunk, once its DMA has landed
+  int prev_l = 0, prev_s = 0, prev_e = 0;
+  auto drain_prev = [&](int b) -> bool {   // pinned[b] -> host chunks, once its DMA has landed
     XFER_HIP(hipEventSynchronize(x->ev_off_dma[b]), err, text);
-    x->pool_off->copy(prev_dst, x->pin_off[b], (size_t)prev_bytes);
+    const char* pin = static_cast<const char*>(x->pin_off[b]);
+    for (int r = prev_s; r < prev_e; ++r) {
+      const int64_t rb = (t.tok[r + 1] - t.tok[r]) * t.row_bytes;
+      if (rb > 0) x->pool_off->copy(t.host[(size_t)prev_l * t.num_segs + r], pin + (t.tok[r] - t.tok[prev_s]) * t.row_bytes, (size_t)rb);
+    }
     return true;
   };
   for (int l = 0; l < L; ++l) {
@@ -273,18 +298,24 @@ bool run_offload(mts_xfer* x, const Task& t, int32_t& err, char (&text)[256]) {
       snprintf(text, sizeof(text), "mts_kv_pack of layer %d: %s", l, mts_last_error());
       return false;
     }
-    for (int s = 0; s < t.num_segs; ++s) {
-      const int64_t bytes = (t.tok[s + 1] - t.tok[s]) * t.row_bytes;
-      if (bytes == 0) continue;
-      const int b = k & 1;
-      XFER_HIP(hipMemcpyAsync(x->pin_off[b], region + l * layer_bytes + t.tok[s] * t.row_bytes, (size_t)bytes,
-                              hipMemcpyDeviceToHost, x->s_offload), err, text);
-      XFER_HIP(hipEventRecord(x->ev_off_dma[b], x->s_offload), err, text);
-      if (have_prev && !drain_prev(b ^ 1)) return false;      // overlaps the copy just enqueued
-      prev_dst = t.host[(size_t)l * t.num_segs + s];
-      prev_bytes = bytes;
-      have_prev = true;
-      ++k;
+    for (int s = 0; s < t.num_segs;) {      // consecutive runs, as many as fit one pinned buffer, per DMA
+      int e = s;
+      int64_t bytes = 0;
+      while (e < t.num_segs && (e == s || bytes + (t.tok[e + 1] - t.tok[e]) * t.row_bytes <= x->cfg.pinned_bytes)) {
+        bytes += (t.tok[e + 1] - t.tok[e]) * t.row_bytes;
+        ++e;
+      }
+      if (bytes > 0) {
+        const int b = k & 1;
+        XFER_HIP(hipMemcpyAsync(x->pin_off[b], region + l * layer_bytes + t.tok[s] * t.row_bytes, (size_t)bytes,
+                                hipMemcpyDeviceToHost, x->s_offload), err, text);
+        XFER_HIP(hipEventRecord(x->ev_off_dma[b], x->s_offload), err, text);
+        if (have_prev && !drain_prev(b ^ 1)) return false;      // overlaps the copy just enqueued
+        prev_l = l; prev_s = s; prev_e = e;
+        have_prev = true;
+        ++k;
+      }
+      s = e;
     }
   }
   if (have_prev && !drain_prev((k - 1) & 1)) return false;

@@ -26,7 +26,8 @@ def _history_runs(w, data, users, chunk):
     return segs, arrays
 
 
-def test_onload_then_per_layer_wait_then_attention_twice():
+@pytest.mark.parametrize("runs_per_dma", [1, 3])
+def test_onload_then_per_layer_wait_then_attention_twice(runs_per_dma):
     import torch
     import gpu_harness as G
     import paper_2604_22881_amd as mts
@@ -35,7 +36,7 @@ def test_onload_then_per_layer_wait_then_attention_twice():
     w = W.custom_workload("xfer", 41, "bf16", 3, 2, 64, 16, [700, 33, 2100, 0, 256], [5, 9, 3, 12, 1],
                           chunk_tokens=chunk)
     row = 2 * w.heads * w.head_dim * 2
-    xfer = mts.mts_xfer_create(pinned_bytes=chunk * row, num_layers=w.layers, copy_threads=3)
+    xfer = mts.mts_xfer_create(pinned_bytes=runs_per_dma * chunk * row, num_layers=w.layers, copy_threads=3)
     try:
         step = G.GpuStep(w, fill_byte=FILL)
         compute = torch.cuda.Stream(device=G.DEV)
@@ -115,7 +116,8 @@ def test_offload_writes_host_chunks_and_admission_control_refuses_what_does_not_
     assert all((a == 0xABCD).all() for la in arrays for a in la)
 
     # (b) accepted: gather -> pinned ping-pong -> host arrays, twice in a row through one pipeline
-    xfer = mts.mts_xfer_create(pinned_bytes=chunk * row, num_layers=w.layers, offload_arena_bytes=2 * arena,
+    # pinned buffers of 2.5 runs: consecutive runs share a DMA, two at a time
+    xfer = mts.mts_xfer_create(pinned_bytes=chunk * row * 5 // 2, num_layers=w.layers, offload_arena_bytes=2 * arena,
                                offload_quota_tokens=2 * tokens, copy_threads=2)
     try:
         arrays2 = [[np.zeros_like(a) for a in la] for la in arrays]
