@@ -298,6 +298,10 @@ int32_t mts_cm_destroy(mts_cm* m);
 /* Tokens of history cached for `user` on either tier; 0 for an unknown user (Alg. 1 step 1). */
 int32_t mts_cm_cached_length(mts_cm* m, int64_t user);
 
+/* Registers a user whose history of total_len tokens lies, whole, in the host tier (e.g. at
+ * start-up, from a persisted store).  The user must not be tracked yet. */
+int32_t mts_cm_import_history(mts_cm* m, int64_t user, int32_t total_len);
+
 /*
  * Page allocation and LRU for one batch (Alg. 1 steps 2 and 6).  For request i (users[i]
  * distinct, new_tokens[i] >= 0) the user is given ceil((total_len + new_tokens[i]) / page_size)

@@ -43,6 +43,11 @@ class CacheModel:
     def pages_for(self, n: int) -> int:
         return -(-n // self.S)
 
+    def import_history(self, user, total_len: int):
+        """A user whose whole history is persisted in the host tier and absent from the GPU."""
+        assert user not in self.total
+        self.total[user] = self.host[user] = total_len
+
     def cached_length(self, user) -> int:
         return self.total.get(user, 0)
 

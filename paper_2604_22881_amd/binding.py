@@ -24,7 +24,7 @@ EXPORTS = (
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
     "mts_xfer_create", "mts_xfer_destroy", "mts_xfer_onload_submit", "mts_xfer_onload_wait_layer",
     "mts_xfer_offload_submit", "mts_xfer_offload_pending_tokens", "mts_xfer_drain",
-    "mts_cm_create", "mts_cm_destroy", "mts_cm_cached_length", "mts_cm_prepare_batch", "mts_cm_commit_batch",
+    "mts_cm_create", "mts_cm_destroy", "mts_cm_import_history", "mts_cm_cached_length", "mts_cm_prepare_batch", "mts_cm_commit_batch",
     "mts_cm_offload_due", "mts_cm_offload_done", "mts_cm_set_locked", "mts_cm_take_evicted", "mts_cm_get_stats",
 )
 
@@ -100,6 +100,7 @@ def lib():
         "mts_cm_create": (I32, [I32, I32, I32, C.POINTER(P)]),
         "mts_cm_destroy": (I32, [P]),
         "mts_cm_cached_length": (I32, [P, I64]),
+        "mts_cm_import_history": (I32, [P, I64, I32]),
         "mts_cm_prepare_batch": (I32, [P, P, P, I32, P, P, P, P, I64]),
         "mts_cm_commit_batch": (I32, [P]),
         "mts_cm_offload_due": (I32, [P, P, P, P, I32]),
@@ -256,6 +257,9 @@ class CacheManager:
             self._h = None
 
     __del__ = close
+
+    def import_history(self, user, total_len):
+        return _check(lib().mts_cm_import_history(self._h, int(user), int(total_len)))
 
     def cached_length(self, user):
         return _check(lib().mts_cm_cached_length(self._h, int(user)))

@@ -101,6 +101,17 @@ int32_t mts_cm_cached_length(mts_cm* m, int64_t user) {
   return it == m->users.end() ? 0 : it->second->total_len;
 }
 
+int32_t mts_cm_import_history(mts_cm* m, int64_t user, int32_t total_len) {
+  if (!m) return mts::set_error(MTS_ERR_INVALID_ARG, "manager is NULL");
+  if (total_len < 0) return mts::set_error(MTS_ERR_INVALID_ARG, "total_len is negative");
+  if (m->users.count(user)) return mts::set_error(MTS_ERR_INVALID_ARG, "user %lld is already tracked", (long long)user);
+  User* u = new User;
+  u->id = user;
+  u->total_len = u->host_len = total_len;      // all of it persisted in the host tier, none on the GPU
+  m->users.emplace(user, u);
+  return MTS_OK;
+}
+
 int32_t mts_cm_prepare_batch(mts_cm* m, const int64_t* users, const int32_t* new_tokens, int32_t batch,
                              int32_t* prefix_lens, int32_t* onload_lens, int32_t* page_indptr,
                              int32_t* page_indices, int64_t page_capacity) {

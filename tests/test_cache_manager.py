@@ -105,6 +105,24 @@ def test_manager_matches_model_on_random_traces():
         cm.close()
 
 
+def test_imported_histories_are_host_hits_with_everything_to_bring_up():
+    cm = mts.CacheManager(20, 4, 8)
+    model = CacheModel(20, 4, 8)
+    for u, n in ((5, 30), (6, 0), (7, 9)):
+        cm.import_history(u, n); model.import_history(u, n)
+    with pytest.raises(mts.MtsError):
+        cm.import_history(5, 1)
+    assert [cm.cached_length(u) for u in (5, 6, 7, 8)] == [30, 0, 9, 0]
+    want = model.prepare_batch([5, 6, 7], [2, 3, 0])
+    prefix, onload, indptr, indices = cm.prepare_batch([5, 6, 7], [2, 3, 0])
+    assert (prefix.tolist(), onload.tolist(), np.diff(indptr).tolist()) == want == ([30, 0, 9], [30, 0, 9], [8, 1, 3])
+    cm.commit_batch(); model.commit_batch()
+    st = cm.stats()
+    assert st["host_hits"] == 2 and st["cold_requests"] == 1 and st["gpu_hits"] == 0
+    # nothing new is due for user 7 (9 persisted, 9 cached); user 5 has 2 fresh tokens < one chunk
+    assert cm.offload_due()[0].tolist() == [] == [d[0] for d in model.offload_due()]
+
+
 def test_manager_eviction_order_matches_model():
     cm = mts.CacheManager(12, 4, 1 << 20)
     model = CacheModel(12, 4, 1 << 20)
