@@ -400,7 +400,8 @@ def main():
                for _ in range(L)]                        # onload buffer contents, one per layer
     evict = [] if args.no_evict else [int(u) for u in w.evict_users]
     evict_segs = SegmentList.for_histories(evict, [w.total_lens[u] for u in evict], w.chunk_tokens, dev)
-    offload = torch.empty(max(evict_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
+    offload = torch.empty(L, max(evict_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
+    offload_stride = offload.stride(0) * offload.element_size()
 
     compute = torch.cuda.Stream(device=dev)
     side = torch.cuda.Stream(device=dev)
@@ -432,12 +433,12 @@ def main():
                 b.record(compute)
             if evict_segs.num_segs and args.pack_per_layer:
                 side.wait_event(ev_appended[l])
-                mts.mts_kv_pack(cache.desc, l, offload, *evict_segs.args(), batch.meta, stream=ss)
+                mts.mts_kv_pack(cache.desc, l, offload[l], *evict_segs.args(), batch.meta, stream=ss)
         if evict_segs.num_segs and not args.pack_per_layer:
-            # Alg. 1 step 9: the offload is submitted after the layer loop, behind the last append
+            # Alg. 1 step 9: the offload is submitted after the layer loop, behind the last append;
+            # every layer's runs are gathered by one launch
             side.wait_event(ev_appended[L - 1])
-            for l in range(L):
-                mts.mts_kv_pack(cache.desc, l, offload, *evict_segs.args(), batch.meta, stream=ss)
+            mts.mts_kv_pack_layers(cache.desc, 0, L, offload, offload_stride, *evict_segs.args(), batch.meta, stream=ss)
 
     for _ in range(args.warmup):
         step()

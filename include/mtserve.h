@@ -139,6 +139,25 @@ int32_t mts_kv_pack(const mts_cache_desc* cache, int32_t layer, void* staging_ou
                     const mts_batch_meta* meta, void* stream);
 
 /*
+ * The same two operations for `layer_count` consecutive layers, starting at `layer_begin`, in
+ * ONE launch: the runs of layer layer_begin + i lie i * staging_layer_stride_bytes further in the
+ * staging buffer (the stride a multiple of 16).  A restored or offloaded user costs a few
+ * megabytes per layer, which a launch per layer moves in little more than its fixed cost; this
+ * is the variant for callers that do not need one event per layer (the offload after the layer
+ * loop, Alg. 1 step 9; a restore that is awaited as a whole).  layer_count == 0 is a no-op.
+ */
+int32_t mts_kv_unpack_layers(const mts_cache_desc* cache, int32_t layer_begin, int32_t layer_count,
+                             const void* staging, int64_t staging_layer_stride_bytes, int32_t num_segs,
+                             const int32_t* seg_user, const int32_t* seg_pos,
+                             const int64_t* seg_tok_indptr, int32_t max_seg_tokens,
+                             const mts_batch_meta* meta, void* stream);
+int32_t mts_kv_pack_layers(const mts_cache_desc* cache, int32_t layer_begin, int32_t layer_count,
+                           void* staging_out, int64_t staging_layer_stride_bytes, int32_t num_segs,
+                           const int32_t* seg_user, const int32_t* seg_pos,
+                           const int64_t* seg_tok_indptr, int32_t max_seg_tokens,
+                           const mts_batch_meta* meta, void* stream);
+
+/*
  * Cache Update (Sec. 3.2 step 5; Alg. 1 step 8.2).  k_new / v_new are device [total_new][H][D]
  * (16-byte aligned), ragged over users by meta->new_indptr; user u's i-th row is written at
  * token position prefix_lens[u] + i of layer `layer`.  The pages must already be in the
@@ -209,8 +228,8 @@ int32_t mts_stage_d2h_async(void* host_dst, const void* device_src, int64_t byte
  * as layer l is scattered, while deeper layers are still on the bus.
  *
  * Offload of a step: after the work already enqueued on `after_stream` (the step's appends),
- * every layer's runs are gathered by mts_kv_pack into a transient buffer from the arena
- * (offload stream), copied to the pinned buffers in turn, and copied from there into the
+ * every layer's runs are gathered by one mts_kv_pack_layers launch into a transient buffer
+ * from the arena (offload stream), copied to the pinned buffers in turn, and copied from there into the
  * caller's host chunks by the copy threads while the next buffer is in flight.  A task is
  * refused with MTS_ERR_BUSY, before anything is enqueued, if the tokens pending in transient
  * buffers would exceed the quota or the arena has no room.

@@ -20,6 +20,7 @@ MTS_F32, MTS_BF16 = 0, 1
 
 EXPORTS = (
     "mts_page_bytes", "mts_pages_for", "mts_elem_offset", "mts_kv_unpack", "mts_kv_pack",
+    "mts_kv_unpack_layers", "mts_kv_pack_layers",
     "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_pointwise",
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
     "mts_xfer_create", "mts_xfer_destroy", "mts_xfer_onload_submit", "mts_xfer_onload_wait_layer",
@@ -84,6 +85,8 @@ def lib():
         "mts_elem_offset": (I64, [DESC, I32, I32, I32, I32]),
         "mts_kv_unpack": (I32, [DESC, I32, P, I32, P, P, P, I32, META, P]),
         "mts_kv_pack": (I32, [DESC, I32, P, I32, P, P, P, I32, META, P]),
+        "mts_kv_unpack_layers": (I32, [DESC, I32, I32, P, I64, I32, P, P, P, I32, META, P]),
+        "mts_kv_pack_layers": (I32, [DESC, I32, I32, P, I64, I32, P, P, P, I32, META, P]),
         "mts_kv_append": (I32, [DESC, I32, P, P, META, P]),
         "mts_attn_workspace_bytes": (I64, [DESC, META]),
         "mts_attn_incremental": (I32, [DESC, I32, P, P, META, F32, P, I64, P]),
@@ -182,6 +185,22 @@ def mts_kv_pack(desc, layer, staging_out, num_segs, seg_user, seg_pos, seg_tok_i
     return _check(lib().mts_kv_pack(C.byref(desc), layer, _ptr(staging_out), num_segs, _ptr(seg_user),
                                     _ptr(seg_pos), _ptr(seg_tok_indptr), max_seg_tokens,
                                     C.byref(meta), _stream(stream)))
+
+
+def mts_kv_unpack_layers(desc, layer_begin, layer_count, staging, staging_layer_stride_bytes, num_segs,
+                         seg_user, seg_pos, seg_tok_indptr, max_seg_tokens, meta, stream=None):
+    return _check(lib().mts_kv_unpack_layers(C.byref(desc), layer_begin, layer_count, _ptr(staging),
+                                             staging_layer_stride_bytes, num_segs, _ptr(seg_user),
+                                             _ptr(seg_pos), _ptr(seg_tok_indptr), max_seg_tokens,
+                                             C.byref(meta), _stream(stream)))
+
+
+def mts_kv_pack_layers(desc, layer_begin, layer_count, staging_out, staging_layer_stride_bytes, num_segs,
+                       seg_user, seg_pos, seg_tok_indptr, max_seg_tokens, meta, stream=None):
+    return _check(lib().mts_kv_pack_layers(C.byref(desc), layer_begin, layer_count, _ptr(staging_out),
+                                           staging_layer_stride_bytes, num_segs, _ptr(seg_user),
+                                           _ptr(seg_pos), _ptr(seg_tok_indptr), max_seg_tokens,
+                                           C.byref(meta), _stream(stream)))
 
 
 def mts_kv_append(desc, layer, k_new, v_new, meta, stream=None):

@@ -228,6 +228,51 @@ int32_t mts_kv_pack(const mts_cache_desc* cache, int32_t layer, void* staging_ou
   return hip_status(mts::launch_pack(g, staging_out, s, b, static_cast<hipStream_t>(stream)), "mts_kv_pack launch");
 }
 
+// mts_kv_unpack_layers / mts_kv_pack_layers
+static int32_t move_layers(bool pack, const mts_cache_desc* cache, int32_t layer_begin, int32_t layer_count, void* staging,
+                    int64_t staging_layer_stride_bytes, int32_t num_segs, const int32_t* seg_user,
+                    const int32_t* seg_pos, const int64_t* seg_tok_indptr, int32_t max_seg_tokens,
+                    const mts_batch_meta* meta, void* stream) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  mts::SegDev s{};
+  int32_t st;
+  if (layer_count < 0) return fail(MTS_ERR_INVALID_ARG, "layer_count is negative");
+  if ((st = check_cache(cache, layer_begin, true, &g)) != MTS_OK) return st;
+  if (layer_count > cache->num_layers - layer_begin)
+    return fail(MTS_ERR_INVALID_ARG, "layers [%d, %d) exceed the cache's %d layers", layer_begin,
+                layer_begin + layer_count, cache->num_layers);
+  if ((st = check_meta(meta, false, true, &b)) != MTS_OK) return st;
+  if ((st = check_segs(num_segs, seg_user, seg_pos, seg_tok_indptr, max_seg_tokens, &s)) != MTS_OK) return st;
+  if (num_segs == 0 || max_seg_tokens == 0 || layer_count == 0) return MTS_OK;
+  if (!staging) return fail(MTS_ERR_INVALID_ARG, "staging is NULL");
+  if (!aligned(staging, 16) || (staging_layer_stride_bytes & 15) || staging_layer_stride_bytes < 0)
+    return fail(MTS_ERR_INVALID_ARG, "staging and its layer stride must be multiples of 16 bytes");
+  if (b.batch == 0) return fail(MTS_ERR_SHAPE, "segments given for an empty batch");
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const hipError_t e = pack ? mts::launch_pack(g, staging, s, b, hs, layer_count, cache->layer_stride_bytes,
+                                               staging_layer_stride_bytes)
+                            : mts::launch_unpack(g, staging, s, b, hs, layer_count, cache->layer_stride_bytes,
+                                                 staging_layer_stride_bytes);
+  return hip_status(e, pack ? "mts_kv_pack_layers launch" : "mts_kv_unpack_layers launch");
+}
+
+int32_t mts_kv_unpack_layers(const mts_cache_desc* cache, int32_t layer_begin, int32_t layer_count,
+                             const void* staging, int64_t staging_layer_stride_bytes, int32_t num_segs,
+                             const int32_t* seg_user, const int32_t* seg_pos, const int64_t* seg_tok_indptr,
+                             int32_t max_seg_tokens, const mts_batch_meta* meta, void* stream) {
+  return move_layers(false, cache, layer_begin, layer_count, const_cast<void*>(staging), staging_layer_stride_bytes,
+                     num_segs, seg_user, seg_pos, seg_tok_indptr, max_seg_tokens, meta, stream);
+}
+
+int32_t mts_kv_pack_layers(const mts_cache_desc* cache, int32_t layer_begin, int32_t layer_count,
+                           void* staging_out, int64_t staging_layer_stride_bytes, int32_t num_segs,
+                           const int32_t* seg_user, const int32_t* seg_pos, const int64_t* seg_tok_indptr,
+                           int32_t max_seg_tokens, const mts_batch_meta* meta, void* stream) {
+  return move_layers(true, cache, layer_begin, layer_count, staging_out, staging_layer_stride_bytes, num_segs,
+                     seg_user, seg_pos, seg_tok_indptr, max_seg_tokens, meta, stream);
+}
+
 int32_t mts_kv_append(const mts_cache_desc* cache, int32_t layer, const void* k_new, const void* v_new,
                       const mts_batch_meta* meta, void* stream) {
   mts::PoolGeom g{};

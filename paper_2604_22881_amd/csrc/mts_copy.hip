@@ -38,7 +38,8 @@ template <typename T, int MODE, int DCH>
 __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, BatchDev b,
                                                       const T* __restrict__ src_a,
                                                       const T* __restrict__ src_b,
-                                                      T* __restrict__ dst_contig, int bulk_blocks) {
+                                                      T* __restrict__ dst_contig, int bulk_blocks,
+                                                      int64_t pool_layer_stride, int64_t contig_layer_stride) {
   constexpr int G = 16 / sizeof(T);
   constexpr int D = DCH * G;
   constexpr int PITCH = D + G;       // LDS row pitch in elements (one granule of padding)
@@ -47,6 +48,10 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
   constexpr int dch = DCH;
   const int HC = H * dch;
   const int s = blockIdx.y;
+  // several layers in one launch (unpack / pack): blockIdx.z picks the layer on both sides
+  g.layer_base += (int64_t)blockIdx.z * pool_layer_stride;
+  src_a += (int64_t)blockIdx.z * contig_layer_stride;
+  if (MODE == MODE_PACK) dst_contig += (int64_t)blockIdx.z * contig_layer_stride;
 
   // Resolve the run: user, first pool token, length, and the contiguous K / V planes.  The
   // loads are ordered so that as few of them as possible wait for one another: nothing below
@@ -294,16 +299,20 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
 
 template <typename T, int MODE, int DCH>
 void launch_typed(const PoolGeom& g, const SegDev& segs, const BatchDev& b, dim3 grid, int bulk_blocks,
-                  const void* a, const void* bsrc, void* dst, hipStream_t stream) {
+                  const void* a, const void* bsrc, void* dst, int64_t pool_layer_stride,
+                  int64_t contig_layer_stride_bytes, hipStream_t stream) {
   hipLaunchKernelGGL((kv_move_kernel<T, MODE, DCH>), grid, dim3(256, 1, 1), 0, stream, g, segs, b, (const T*)a,
-                     (const T*)bsrc, (T*)dst, bulk_blocks);
+                     (const T*)bsrc, (T*)dst, bulk_blocks, pool_layer_stride,
+                     contig_layer_stride_bytes / (int64_t)sizeof(T));
 }
 
 template <int MODE>
 hipError_t launch_move(const PoolGeom& g, const SegDev& segs, const BatchDev& b, int runs,
                        int64_t max_run_tokens, const void* a, const void* bsrc, void* dst,
-                       hipStream_t stream) {
-  if (runs <= 0 || max_run_tokens <= 0) return hipSuccess;
+                       hipStream_t stream, int layers = 1, int64_t pool_layer_stride = 0,
+                       int64_t contig_layer_stride_bytes = 0) {
+  if (runs <= 0 || max_run_tokens <= 0 || layers <= 0) return hipSuccess;
+  if (layers > 65535) return hipErrorInvalidValue;
   const int G = 16 / g.es;
   // Runs of at least 128 tokens: whole sub-blocks of the longest run x heads, one per wavefront,
   // then the groups of at most two partly covered sub-blocks per run (2 * 16/G groups, + 2).
@@ -316,10 +325,11 @@ hipError_t launch_move(const PoolGeom& g, const SegDev& segs, const BatchDev& b,
   const int64_t edge_work = edge_groups * (int64_t)g.H * (g.D / G);
   const int64_t blocks = bulk_blocks + (edge_work + 255) / 256;
   if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
-  dim3 grid((unsigned)blocks, (unsigned)runs, 1);
+  dim3 grid((unsigned)blocks, (unsigned)runs, (unsigned)layers);
   const int dch = g.D / G;
 #define MTS_MOVE_CASE(T, DCH_) \
-  case DCH_: launch_typed<T, MODE, DCH_>(g, segs, b, grid, (int)bulk_blocks, a, bsrc, dst, stream); break;
+  case DCH_: launch_typed<T, MODE, DCH_>(g, segs, b, grid, (int)bulk_blocks, a, bsrc, dst, pool_layer_stride, \
+                                         contig_layer_stride_bytes, stream); break;
   if (g.es == 2) {
     switch (dch) {
       MTS_MOVE_CASE(uint16_t, 4) MTS_MOVE_CASE(uint16_t, 8) MTS_MOVE_CASE(uint16_t, 16)
@@ -337,16 +347,16 @@ hipError_t launch_move(const PoolGeom& g, const SegDev& segs, const BatchDev& b,
 
 }  // namespace
 
-hipError_t launch_unpack(const PoolGeom& g, const void* staging, const SegDev& segs,
-                         const BatchDev& b, hipStream_t stream) {
+hipError_t launch_unpack(const PoolGeom& g, const void* staging, const SegDev& segs, const BatchDev& b,
+                         hipStream_t stream, int layers, int64_t pool_layer_stride, int64_t staging_layer_stride) {
   return launch_move<MODE_UNPACK>(g, segs, b, segs.num_segs, segs.max_seg_tokens, staging, nullptr,
-                                  nullptr, stream);
+                                  nullptr, stream, layers, pool_layer_stride, staging_layer_stride);
 }
 
-hipError_t launch_pack(const PoolGeom& g, void* staging_out, const SegDev& segs,
-                       const BatchDev& b, hipStream_t stream) {
+hipError_t launch_pack(const PoolGeom& g, void* staging_out, const SegDev& segs, const BatchDev& b,
+                       hipStream_t stream, int layers, int64_t pool_layer_stride, int64_t staging_layer_stride) {
   return launch_move<MODE_PACK>(g, segs, b, segs.num_segs, segs.max_seg_tokens, staging_out, nullptr,
-                                staging_out, stream);
+                                staging_out, stream, layers, pool_layer_stride, staging_layer_stride);
 }
 
 hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new,

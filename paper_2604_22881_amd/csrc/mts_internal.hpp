@@ -31,10 +31,14 @@ struct SegDev {              // segment lists of unpack / pack
   int32_t        max_seg_tokens;
 };
 
-hipError_t launch_unpack(const PoolGeom& g, const void* staging, const SegDev& segs,
-                         const BatchDev& b, hipStream_t stream);
-hipError_t launch_pack(const PoolGeom& g, void* staging_out, const SegDev& segs,
-                       const BatchDev& b, hipStream_t stream);
+// `layers` consecutive layers starting at g.layer_base in one launch: layer i of the pool lies
+// i * pool_layer_stride bytes further, its runs i * staging_layer_stride bytes further.
+hipError_t launch_unpack(const PoolGeom& g, const void* staging, const SegDev& segs, const BatchDev& b,
+                         hipStream_t stream, int layers = 1, int64_t pool_layer_stride = 0,
+                         int64_t staging_layer_stride = 0);
+hipError_t launch_pack(const PoolGeom& g, void* staging_out, const SegDev& segs, const BatchDev& b,
+                       hipStream_t stream, int layers = 1, int64_t pool_layer_stride = 0,
+                       int64_t staging_layer_stride = 0);
 hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new,
                          const BatchDev& b, hipStream_t stream);
 

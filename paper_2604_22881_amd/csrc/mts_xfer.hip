@@ -290,14 +290,15 @@ bool run_offload(mts_xfer* x, const Task& t, int32_t& err, char (&text)[256]) {
     }
     return true;
   };
+  // one gather launch for all layers (the region holds them layer after layer), then the DMAs
+  const int32_t st = mts_kv_pack_layers(&t.cache, 0, L, region, layer_bytes, t.num_segs, t.seg_user, t.seg_pos,
+                                        t.seg_tok_indptr, t.max_seg_tokens, &t.meta, x->s_offload);
+  if (st != MTS_OK) {
+    err = st;
+    snprintf(text, sizeof(text), "mts_kv_pack_layers: %s", mts_last_error());
+    return false;
+  }
   for (int l = 0; l < L; ++l) {
-    const int32_t st = mts_kv_pack(&t.cache, l, region + l * layer_bytes, t.num_segs, t.seg_user, t.seg_pos,
-                                   t.seg_tok_indptr, t.max_seg_tokens, &t.meta, x->s_offload);
-    if (st != MTS_OK) {
-      err = st;
-      snprintf(text, sizeof(text), "mts_kv_pack of layer %d: %s", l, mts_last_error());
-      return false;
-    }
     for (int s = 0; s < t.num_segs;) {      // consecutive runs, as many as fit one pinned buffer, per DMA
       int e = s;
       int64_t bytes = 0;

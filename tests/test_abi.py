@@ -152,6 +152,23 @@ def test_bad_segments_are_rejected():
     assert _code(mts.mts_stage_d2h_async, FAKE, FAKE, -1, stream=0) == B.MTS_ERR_INVALID_ARG
 
 
+def test_bad_layer_ranges_are_rejected():
+    d, m = _desc(), _meta()          # the descriptor has 2 layers
+    for fn in (mts.mts_kv_unpack_layers, mts.mts_kv_pack_layers):
+        assert _code(fn, d, 0, 3, FAKE, 4096, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 1, 2, FAKE, 4096, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 2, 0, FAKE, 4096, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 0, -1, FAKE, 4096, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 0, 2, FAKE, 4096 + 8, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 0, 2, FAKE, -4096, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 0, 2, None, 4096, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 0, 2, FAKE, 4096, 2, None, FAKE, FAKE, 4, m, stream=0) == B.MTS_ERR_INVALID_ARG
+        assert _code(fn, d, 0, 2, FAKE, 4096, 2, FAKE, FAKE, FAKE, 4, _meta(batch=0), stream=0) == B.MTS_ERR_SHAPE
+        # nothing to move: accepted without touching a pointer
+        assert fn(d, 0, 0, None, 0, 2, FAKE, FAKE, FAKE, 4, m, stream=0) == 0
+        assert fn(d, 0, 2, None, 0, 0, None, None, None, 0, m, stream=0) == 0
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

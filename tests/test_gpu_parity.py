@@ -350,3 +350,72 @@ def test_data_movement_random_shapes(seed):
         for u, p, n, g in zip(users, pos, cnt, got):
             assert g.tobytes() == oracle.pack(store, 0, w.user_pages(u), p, n).tobytes(), f"pack user {u} [{p},{p+n})"
     assert np.array_equal(step.pool_image(0), G.expected_pool_image(w, store, 0, FILL)), "pack must not write the pool"
+
+
+@pytest.mark.parametrize("dtype,D,S", [("bf16", 64, 16), ("f32", 32, 32), ("bf16", 128, 64)])
+def test_several_layers_in_one_launch(dtype, D, S):
+    """mts_kv_unpack_layers / mts_kv_pack_layers on a range of layers inside a larger cache: the
+    layers of the range hold exactly what the oracle's unpack wrote, the layers outside it and the
+    padding between the per-layer staging blocks stay untouched, and the packed runs equal the
+    oracle's pack bit for bit."""
+    import torch
+    import paper_2604_22881_amd as mts
+    from paper_2604_22881_amd.runtime import SegmentList
+    G = _harness()
+    L, lo, cnt_l = 4, 1, 2
+    prefix, new = [300, 17, 0, 129, 640], [5, 0, 40, 3, 200]
+    w = W.custom_workload("layers", 4242, dtype, L, 3, D, S, prefix, new, chunk_tokens=200)
+    data = draw_step_data(w, layers=range(lo, lo + cnt_l))
+    step = G.GpuStep(w, fill_byte=FILL)
+    H, es = w.heads, w.elem_bytes
+    row = 2 * H * D                                           # elements per token (K and V)
+
+    # ---- unpack: runs of every history, layer blocks `stride` elements apart (padded) ----
+    users = [u for u in range(w.batch) if prefix[u] > 0]
+    segs = SegmentList.for_histories(users, [prefix[u] for u in users], w.chunk_tokens, G.DEV)
+    su, sp, sc = segs.seg_user.cpu().numpy(), segs.seg_pos.cpu().numpy(), np.diff(segs.host_indptr)
+    stride = segs.total_tokens * row + 24                     # 24 elements of padding: 48 or 96 bytes
+    host = np.zeros(cnt_l * stride, dtype=w.np_dtype)
+    for i in range(cnt_l):
+        parts = [np.ascontiguousarray(data["hist"][lo + i][su[s]][:, sp[s]:sp[s] + sc[s]]).reshape(-1)
+                 for s in range(segs.num_segs)]
+        host[i * stride:i * stride + segs.total_tokens * row] = np.concatenate(parts)
+    mts.mts_kv_unpack_layers(step.cache.desc, lo, cnt_l, G.to_dev(host), stride * es, *segs.args(), step.batch.meta)
+    torch.cuda.synchronize()
+    store = _oracle_store(w, data, do_append=False)
+    for l in range(L):
+        assert np.array_equal(step.pool_image(l), G.expected_pool_image(w, store, l, FILL)), f"layer {l} after unpack"
+
+    for l in range(lo, lo + cnt_l):
+        step.append(data, l)
+    store = _oracle_store(w, data, do_append=True)
+
+    # ---- pack: random sub-ranges and whole users, all layers of the range in one launch ----
+    rng = np.random.default_rng(9)
+    pu, pp, pc = [], [], []
+    for u in range(w.batch):
+        T = int(w.total_lens[u])
+        if T == 0:
+            continue
+        a = int(rng.integers(0, T)); n = int(rng.integers(1, T - a + 1))
+        pu += [u, u]; pp += [0, a]; pc += [T, n]
+    psegs = SegmentList(pu, pp, pc, G.DEV)
+    pstride = psegs.total_tokens * row + 8
+    guard = 12345 if dtype == "bf16" else 0.5
+    out = torch.full((cnt_l * pstride,), guard, dtype=torch.float32 if dtype == "f32" else torch.int16, device=G.DEV)
+    mts.mts_kv_pack_layers(step.cache.desc, lo, cnt_l, out, pstride * es, *psegs.args(), step.batch.meta)
+    torch.cuda.synchronize()
+    flat = G.to_host(out, w.np_dtype)
+    for i in range(cnt_l):
+        off = i * pstride
+        for u, p, n in zip(pu, pp, pc):
+            want = oracle.pack(store, lo + i, w.user_pages(u), p, n)
+            assert flat[off:off + want.size].tobytes() == want.tobytes(), f"layer {lo + i} user {u} [{p},{p + n})"
+            off += want.size
+        pad = flat[off:(i + 1) * pstride]
+        assert pad.size == 8 and (pad == flat.dtype.type(guard)).all(), "padding between layers was written"
+        # the one-layer call returns the same bytes
+        single = step.pack(lo + i, pu, pp, pc)
+        assert b"".join(g.tobytes() for g in single) == flat[i * pstride:i * pstride + psegs.total_tokens * row].tobytes()
+    for l in range(L):
+        assert np.array_equal(step.pool_image(l), G.expected_pool_image(w, store, l, FILL)), f"layer {l} after pack"
