@@ -205,6 +205,33 @@ int32_t mts_attn_pointwise(const mts_cache_desc* cache, int32_t layer, const voi
                            const mts_batch_meta* meta, float sm_scale, float inv_norm,
                            void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * The same two attentions for a layer whose append has not happened: the context of user u is
+ * the cached prefix in the pool (positions 0 .. prefix_lens[u]-1) followed by this step's rows
+ * taken from k_new / v_new directly (Sec. 2: K = [K_pre ; k_delta], V = [V_pre ; v_delta]).  The
+ * result equals mts_kv_append followed by mts_attn_incremental / mts_attn_pointwise, but the call
+ * does not read the pool's slots of the new tokens, so mts_kv_append of the same layer may run
+ * on another stream at the same time (or later): the copy leaves the layer's critical path.
+ * The caller still appends before anything else reads those slots (the next step, a pack).
+ *   k_new, v_new   device [total_new][H][D], cache dtype, 16-byte aligned, as for mts_kv_append
+ * For long new segments (the shapes served by the dense-prefill kernel) and for fp32 caches
+ * every key is read from the pool: there the call enqueues the append itself, on `stream`,
+ * before the attention (a caller's own append then rewrites the same bytes;
+ * mts_attn_unappended_appends tells which case a shape falls in).  Everything else is as for the
+ * two calls above.
+ */
+/* 1 if the two calls below append by themselves for this shape (the caller then skips its own
+ * mts_kv_append), 0 if they leave the pool alone, < 0 on a bad descriptor.  Host only. */
+int32_t mts_attn_unappended_appends(const mts_cache_desc* cache, const mts_batch_meta* meta);
+int32_t mts_attn_incremental_unappended(const mts_cache_desc* cache, int32_t layer, const void* q,
+                                        const void* k_new, const void* v_new, void* out,
+                                        const mts_batch_meta* meta, float sm_scale, void* workspace,
+                                        int64_t workspace_bytes, void* stream);
+int32_t mts_attn_pointwise_unappended(const mts_cache_desc* cache, int32_t layer, const void* q,
+                                      const void* k_new, const void* v_new, void* out,
+                                      const mts_batch_meta* meta, float sm_scale, float inv_norm,
+                                      void* workspace, int64_t workspace_bytes, void* stream);
+
 /* Host<->device staging copies on `stream` (hipMemcpyAsync); `host` should be pinned for the
  * copy to be asynchronous (Sec. 4.2, DMA between pinned buffers and the onload / offload buffers). */
 int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream);

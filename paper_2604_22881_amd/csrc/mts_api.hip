@@ -302,10 +302,17 @@ int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_me
 
 namespace {
 
-// mts_attn_incremental (inv_norm == 0) and mts_attn_pointwise (inv_norm > 0)
+// the streaming kernel addresses the elements of k_new / v_new with 32-bit offsets
+bool rows_fit_32bit(const mts::PoolGeom& g, const mts::BatchDev& b) {
+  return (int64_t)b.total_new * g.H * g.D < (1ll << 31);
+}
+
+// mts_attn_incremental (inv_norm == 0) and mts_attn_pointwise (inv_norm > 0); with `unappended`,
+// the step's K/V rows come from k_new / v_new instead of the pool
 int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
                        const mts_batch_meta* meta, float sm_scale, float inv_norm, void* workspace,
-                       int64_t workspace_bytes, void* stream) {
+                       int64_t workspace_bytes, void* stream, bool unappended = false,
+                       const void* k_new = nullptr, const void* v_new = nullptr) {
   mts::PoolGeom g{};
   mts::BatchDev b{};
   int32_t st;
@@ -316,6 +323,11 @@ int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t la
   if (b.batch == 0 || b.total_new == 0) return MTS_OK;
   if (!q || !out) return fail(MTS_ERR_INVALID_ARG, "q / out is NULL");
   if (!aligned(q, 16) || !aligned(out, 16)) return fail(MTS_ERR_INVALID_ARG, "q / out is not 16-byte aligned");
+  if (unappended) {
+    if (!k_new || !v_new) return fail(MTS_ERR_INVALID_ARG, "k_new / v_new is NULL");
+    if (!aligned(k_new, 16) || !aligned(v_new, 16))
+      return fail(MTS_ERR_INVALID_ARG, "k_new / v_new is not 16-byte aligned");
+  }
   const mts::AttnPlan plan = mts::plan_attention(g, b);
   if (plan.too_large)
     return fail(MTS_ERR_UNSUPPORTED, "batch %d exceeds 4096 users, batch x ceil(max_new %d / 64) exceeds 16384 "
@@ -329,11 +341,19 @@ int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t la
   }
   const float scale = sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)g.D);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (plan.use_mfma && plan.use_prefill && !getenv("MTS_ATTN_PLAIN"))
+  const bool plain = getenv("MTS_ATTN_PLAIN") != nullptr;
+  if (plan.use_mfma && !plan.use_prefill && !plain && !(unappended && !rows_fit_32bit(g, b)))
+    return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, inv_norm, plan.ws_bytes > 0 ? workspace : nullptr, s,
+                                            unappended ? k_new : nullptr, unappended ? v_new : nullptr), name);
+  // The other kernels read every key from the pool: an unappended call writes the rows there
+  // first, on the same stream (a long new segment or fp32 elements; the copy is a small part
+  // of such a call).
+  if (unappended) {
+    const hipError_t e = mts::launch_append(g, k_new, v_new, b, s);
+    if (e != hipSuccess) return hip_status(e, name);
+  }
+  if (plan.use_mfma && plan.use_prefill && !plain)
     return hip_status(mts::launch_attn_prefill(g, q, out, b, scale, inv_norm, s), name);
-  if (plan.use_mfma && !getenv("MTS_ATTN_PLAIN"))
-    return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, inv_norm, plan.ws_bytes > 0 ? workspace : nullptr, s),
-                      name);
   return hip_status(mts::launch_attn_generic(g, q, out, b, scale, inv_norm, s), name);
 }
 
@@ -355,6 +375,33 @@ int32_t mts_attn_pointwise(const mts_cache_desc* cache, int32_t layer, const voi
     return fail(MTS_ERR_INVALID_ARG, "inv_norm must be finite and > 0");
   return attention_call("mts_attn_pointwise launch", cache, layer, q, out, meta, sm_scale, inv_norm, workspace,
                         workspace_bytes, stream);
+}
+
+int32_t mts_attn_unappended_appends(const mts_cache_desc* cache, const mts_batch_meta* meta) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  int32_t st;
+  if ((st = check_cache(cache, 0, false, &g)) != MTS_OK) return st;
+  if ((st = check_meta(meta, true, false, &b)) != MTS_OK) return st;
+  if (b.batch == 0 || b.total_new == 0) return 0;
+  const mts::AttnPlan plan = mts::plan_attention(g, b);
+  return (plan.use_mfma && !plan.use_prefill && !getenv("MTS_ATTN_PLAIN") && rows_fit_32bit(g, b)) ? 0 : 1;
+}
+
+int32_t mts_attn_incremental_unappended(const mts_cache_desc* cache, int32_t layer, const void* q, const void* k_new,
+                                        const void* v_new, void* out, const mts_batch_meta* meta, float sm_scale,
+                                        void* workspace, int64_t workspace_bytes, void* stream) {
+  return attention_call("mts_attn_incremental_unappended launch", cache, layer, q, out, meta, sm_scale, 0.f, workspace,
+                        workspace_bytes, stream, true, k_new, v_new);
+}
+
+int32_t mts_attn_pointwise_unappended(const mts_cache_desc* cache, int32_t layer, const void* q, const void* k_new,
+                                      const void* v_new, void* out, const mts_batch_meta* meta, float sm_scale,
+                                      float inv_norm, void* workspace, int64_t workspace_bytes, void* stream) {
+  if (!(inv_norm > 0.f) || inv_norm > 1e30f)
+    return fail(MTS_ERR_INVALID_ARG, "inv_norm must be finite and > 0");
+  return attention_call("mts_attn_pointwise_unappended launch", cache, layer, q, out, meta, sm_scale, inv_norm,
+                        workspace, workspace_bytes, stream, true, k_new, v_new);
 }
 
 int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream) {

@@ -35,6 +35,13 @@
 // pointwise aggregation out = inv_norm * sum_j silu(c * q.k_j) v_j: the weights need no
 // statistics at all, so there is no reference max, no denominator and no redo; hidden keys
 // get logit 0 (silu(0) = 0); cut pairs are finished by adding their pieces.
+//
+// Unappended mode (template flag FRESH).  The step's own K/V rows are taken from k_new / v_new
+// ([token][H][D], the layout the projection writes) instead of the pool, so the call does not
+// depend on the layer's append (Sec. 2: the context is the cached prefix followed by the new
+// rows) and the append can run beside it on another stream.  Only the few tiles at the end of
+// a (query tile, head) that hold new tokens take this path: a K fragment is still one 16-byte
+// load per lane (from the token's row), a V^T fragment is gathered element by element.
 #include <math.h>
 
 #include <type_traits>
@@ -49,6 +56,7 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int kTile = 32;       // kv tokens per step (two 16-token sub-blocks)
 constexpr int kWavesPerWg = 4;
@@ -93,9 +101,11 @@ struct MergeDesc {
 };
 
 // WPS = wavefronts per SIMD the kernel is compiled for (bounds its registers)
-template <int D, int NQB, int PF, int WPS, bool PW>
+template <int D, int NQB, int PF, int WPS, bool PW, bool FRESH>
 __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, BatchDev b,
                                                           const uint16_t* __restrict__ q,
+                                                          const uint16_t* __restrict__ k_new,
+                                                          const uint16_t* __restrict__ v_new,
                                                           uint16_t* __restrict__ out, float c, float inv_norm,
                                                           int q_tiles_max, int n_items, int min_tiles,
                                                           MergeDesc* __restrict__ ws_desc,
@@ -234,23 +244,34 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     // Page ids come through scalar loads (their counter is separate from the vector-memory
     // one, so they never force a wait on K/V data in flight).  Ring slot p keeps the ids of
     // the NEXT tile it will load, requested one ring revolution earlier.
-    const int last_tile = t_end - 1;
+    // Unappended mode: the ring serves the tiles that lie in the pool entirely, [t_beg, ring_end);
+    // those with new tokens, [fresh_beg, t_end), follow one by one.
+    const int new_tile0 = P / kTile;                   // first tile that holds a new token
+    int ring_end = t_end;
+    if (FRESH && new_tile0 < ring_end) ring_end = new_tile0 > t_beg ? new_tile0 : t_beg;
+    const int fresh_beg = FRESH ? ring_end : t_end;
+    const int last_tile = ring_end - 1;
     int idr0[PF], idr1[PF];
-    auto page_ids = [&](int tile, int& id0, int& id1) {
-      const int tl = tile < last_tile ? tile : last_tile;        // past the end: repeat the last tile
+    auto page_ids_at = [&](int tl, int& id0, int& id1) __attribute__((always_inline)) {
       int lp0 = (tl * 2) >> g.sub_shift, lp1 = (tl * 2 + 1) >> g.sub_shift;
       if (lp1 >= npg) lp1 = lp0;                                 // no second page at the tail
       if (lp0 >= npg) lp0 = lp1 = 0;                             // metadata out of range: stay in bounds
       id0 = npg > 0 ? b.page_indices[pbeg + lp0] : 0;
       id1 = npg > 0 ? b.page_indices[pbeg + lp1] : 0;
     };
-    auto tile_bases = [&](int tile, int id0, int id1, const char*& kb0, const char*& kb1) {
-      const int tl = tile < last_tile ? tile : last_tile;
+    auto tile_bases_at = [&](int tl, int id0, int id1, const char*& kb0, const char*& kb1) __attribute__((always_inline)) {
       const int sb0 = tl * 2, sb1 = sb0 + 1;
       if ((unsigned)id0 >= (unsigned)g.num_pages) id0 = 0;
       if ((unsigned)id1 >= (unsigned)g.num_pages) id1 = 0;
       kb0 = head_base + (int64_t)id0 * g.page_bytes + (int64_t)(sb0 & sub_mask) * 16 * D * 2;
       kb1 = head_base + (int64_t)id1 * g.page_bytes + (int64_t)(sb1 & sub_mask) * 16 * D * 2;
+    };
+    // the ring's versions: past its end, repeat its last tile
+    auto page_ids = [&](int tile, int& id0, int& id1) __attribute__((always_inline)) {
+      page_ids_at(tile < last_tile ? tile : last_tile, id0, id1);
+    };
+    auto tile_bases = [&](int tile, int id0, int id1, const char*& kb0, const char*& kb1) __attribute__((always_inline)) {
+      tile_bases_at(tile < last_tile ? tile : last_tile, id0, id1, kb0, kb1);
     };
 
     bf16x8 kf[PF][2][KS];
@@ -258,7 +279,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     // Loads tile `tile` (clamped to the segment's last tile, so that the loads of the steady
     // state are unconditional and the hardware's in-order load counter can be waited on
     // exactly) into ring slot p, then requests the ids of the tile this slot loads next.
-    auto issue = [&](auto buf, int tile) {            // buf is an integral_constant: register ring slot
+    auto issue = [&](auto buf, int tile) __attribute__((always_inline)) {            // buf is an integral_constant: register ring slot
       constexpr int p = decltype(buf)::value;
       const char *kb0, *kb1;
       tile_bases(tile, idr0[p], idr1[p], kb0, kb1);
@@ -276,11 +297,77 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         vf[p][db] = *reinterpret_cast<const bf16x8*>(vl + db * 16 * 16 * 2);
       page_ids(tile + PF, idr0[p], idr1[p]);
     };
+    // ---- unappended mode: tiles that hold new tokens -------------------------------------
+    // Token position of the K row this lane loads for half-tile hf of a tile that starts at tb
+    // (the pool's slot order: see the K fragment above), and the address of that token's row in
+    // k_new if it is one of this step's tokens (positions past the user's last token repeat the
+    // last row: every query's mask hides them).
+    const int k_lane_pos = ((r >> 3) << 4) + (((r & 7) >> 2) << 3) + (r & 3);
+    auto fresh_k_row = [&](int kp) __attribute__((always_inline)) -> const char* {
+      int idx = kp - P;
+      idx = idx < n_u - 1 ? idx : n_u - 1;
+      idx = idx > 0 ? idx : 0;
+      return reinterpret_cast<const char*>(k_new + ((int64_t)(tok0 + idx) * H + h) * D + 8 * gq);
+    };
+    // Loads tile `tile` (one with new tokens) into ring slot 0: lanes whose token is new read it
+    // from k_new / v_new, the others from the pool.  These few tiles per (query tile, head) are
+    // taken one at a time after the ring has drained, when its registers are free.
+    auto load_fresh = [&](int tile) __attribute__((always_inline)) {
+      const int tb = tile * kTile;
+      int id0, id1;
+      page_ids_at(tile, id0, id1);
+      const char *kb0, *kb1;
+      tile_bases_at(tile, id0, id1, kb0, kb1);
+      const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int kp = tb + k_lane_pos + 4 * hf;
+        const char* row = fresh_k_row(kp);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          const char* src = (kp >= P) ? row + 32 * s * 2 : kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16;
+          kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(src);
+        }
+      }
+      // V^T: of this lane's 8 tokens, the first n_pool are cached ones (16 bytes from the pool,
+      // as always, masked to those tokens); the others come one element each from v_new through
+      // a buffer descriptor that spans exactly the user's new rows of this head, so that rows
+      // before the first and past the last new token read as 0 without a branch.  All loads are
+      // in flight together.
+      const char* vl = ((gq < 2) ? kb0 : kb1) + v_off + (r * 16 + (gq & 1) * 8) * 2;
+      const int vp = tb + 8 * gq;                      // first of this lane's 8 tokens
+      int n_pool = P - vp;
+      n_pool = n_pool < 0 ? 0 : (n_pool > 8 ? 8 : n_pool);
+      uint32_t pool_mask[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        pool_mask[j] = (2 * j < n_pool ? 0xffffu : 0u) | (2 * j + 1 < n_pool ? 0xffff0000u : 0u);
+        asm volatile("" : "+v"(pool_mask[j]));         // keeps the mask a mask (no branch per load)
+      }
+      const int row_bytes = H * D * 2;
+      const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(v_new + ((int64_t)tok0 * H + h) * D), 0, (n_u - 1) * row_bytes + D * 2, 0x00020000);
+      int idx0 = vp - P;                               // new-token index of the lane's first token
+      idx0 = idx0 > -8 ? idx0 : -8;                    // all 8 before the first new token: stays out of range
+      const int voff0 = idx0 * row_bytes + r * 2;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const u32x4 pool = *reinterpret_cast<const u32x4*>(vl + db * 16 * 16 * 2);
+        uint32_t f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          f[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rows, voff0 + e * row_bytes + 32 * db, 0, 0);
+        u32x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (pool[j] & pool_mask[j]) | f[2 * j] | (f[2 * j + 1] << 16);
+        vf[0][db] = __builtin_bit_cast(bf16x8, v);
+      }
+    };
 
     // S^T of query block qb against the K fragments of ring slot p.  The lane holds, for query
     // q0+16*qb+r, keys tb + 8*gq + {0..3} (s0) and {4..7} (s1); with `masked`, keys the query
     // must not see (causal order among the new tokens) are set to -inf.
-    auto scores = [&](auto buf, int qb, int tb, bool masked, f32x4& s0, f32x4& s1) {
+    auto scores = [&](auto buf, int qb, int tb, bool masked, f32x4& s0, f32x4& s1) __attribute__((always_inline)) {
       constexpr int p = decltype(buf)::value;
       s0 = f32x4{0.f, 0.f, 0.f, 0.f};
       s1 = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -309,7 +396,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     // softmax is shift-invariant, and weights above 1 are as exact in bf16 / fp32 as weights
     // below 1.  TAIL adds what only the causal tail needs: the mask, and zeroing of V slots past
     // the user's last token (they may hold anything).
-    auto tile_step = [&](auto nq_c, auto tail_c, auto buf, int tile) {
+    auto tile_step = [&](auto nq_c, auto tail_c, auto buf, int tile) __attribute__((always_inline)) {
       constexpr int NQ = decltype(nq_c)::value;
       constexpr bool TAIL = decltype(tail_c)::value;
       constexpr int p = decltype(buf)::value;
@@ -350,23 +437,29 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
 
     // Exact running max of every query over the whole segment (K only, no pipelining): used
     // when the first tile's max turned out to be too low a reference.
-    auto exact_max = [&](auto nq_c) {
+    auto exact_max = [&](auto nq_c) __attribute__((always_inline)) {
       constexpr int NQ = decltype(nq_c)::value;
       float mx[NQ];
 #pragma unroll
       for (int qb = 0; qb < NQ; ++qb) mx[qb] = -INFINITY;
       for (int tile = t_beg; tile < t_end; ++tile) {
         int id0, id1;
-        page_ids(tile, id0, id1);
+        page_ids_at(tile, id0, id1);
         const char *kb0, *kb1;
-        tile_bases(tile, id0, id1, kb0, kb1);
+        tile_bases_at(tile, id0, id1, kb0, kb1);
         const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
         const int tb = tile * kTile;
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
+        for (int hf = 0; hf < 2; ++hf) {
+          const int kp = tb + k_lane_pos + 4 * hf;
+          const char* row = FRESH ? fresh_k_row(kp) : nullptr;
 #pragma unroll
-          for (int s = 0; s < KS; ++s)
-            kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16);
+          for (int s = 0; s < KS; ++s) {
+            const char* src = kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16;
+            if (FRESH && kp >= P) src = row + 32 * s * 2;
+            kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(src);
+          }
+        }
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) {
           f32x4 s0, s1;
@@ -383,14 +476,25 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
 
     // tiles [0, fast_stop) hide no key from any query of this tile
     int fast_stop = (first_query_pos + 1) / kTile;
-    if (fast_stop > t_end) fast_stop = t_end;
+    if (fast_stop > ring_end) fast_stop = ring_end;
 
     // The whole segment for NQ query blocks.  Ring slots are integral_constants so that every
     // register array is indexed by constants only; tile t lives in slot (t - t_beg) % PF.
-    auto run_segment = [&](auto nq_c) {
+    auto run_segment = [&](auto nq_c) __attribute__((always_inline)) {
       constexpr int NQ = decltype(nq_c)::value;
       constexpr std::false_type body{};
       constexpr std::true_type tail{};
+      // reference max = max of the segment's first tile (in ring slot 0 when this is called)
+      auto reference_from_slot0 = [&]() __attribute__((always_inline)) {
+        const int tb = t_beg * kTile;
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) {
+          f32x4 s0, s1;
+          scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > first_query_pos, s0, s1);
+          m[qb] = quad_row_max(max8(s0, s1));
+          mcq[qb] = (m[qb] == -INFINITY ? 0.f : m[qb]) * c;    // nothing visible: any reference
+        }
+      };
       for (int attempt = 0; attempt < 2; ++attempt) {
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
@@ -402,59 +506,58 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
           if (attempt == 1) exact_max(nq_c);
         }
 
-        page_ids(t_beg, idr0[0], idr1[0]);
-        if constexpr (PF > 1) page_ids(t_beg + 1, idr0[1], idr1[1]);
-        if constexpr (PF > 2) page_ids(t_beg + 2, idr0[2], idr1[2]);
-        if constexpr (PF > 3) page_ids(t_beg + 3, idr0[3], idr1[3]);
-        issue(std::integral_constant<int, 0>{}, t_beg);
-        if constexpr (PF > 1) issue(std::integral_constant<int, 1>{}, t_beg + 1);
-        if constexpr (PF > 2) issue(std::integral_constant<int, 2>{}, t_beg + 2);
-        if constexpr (PF > 3) issue(std::integral_constant<int, 3>{}, t_beg + 3);
+        if (!FRESH || ring_end > t_beg) {
+          page_ids(t_beg, idr0[0], idr1[0]);
+          if constexpr (PF > 1) page_ids(t_beg + 1, idr0[1], idr1[1]);
+          if constexpr (PF > 2) page_ids(t_beg + 2, idr0[2], idr1[2]);
+          if constexpr (PF > 3) page_ids(t_beg + 3, idr0[3], idr1[3]);
+          issue(std::integral_constant<int, 0>{}, t_beg);
+          if constexpr (PF > 1) issue(std::integral_constant<int, 1>{}, t_beg + 1);
+          if constexpr (PF > 2) issue(std::integral_constant<int, 2>{}, t_beg + 2);
+          if constexpr (PF > 3) issue(std::integral_constant<int, 3>{}, t_beg + 3);
 
-        if (!PW && attempt == 0) {
-          // reference max = max of the segment's first tile (already in ring slot 0)
-          const int tb = t_beg * kTile;
-#pragma unroll
-          for (int qb = 0; qb < NQ; ++qb) {
-            f32x4 s0, s1;
-            scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > first_query_pos, s0, s1);
-            m[qb] = quad_row_max(max8(s0, s1));
-            mcq[qb] = (m[qb] == -INFINITY ? 0.f : m[qb]) * c;    // nothing visible: any reference
+          if (!PW && attempt == 0) reference_from_slot0();
+
+          int tile = t_beg;
+          while (tile + PF <= fast_stop) {                 // steady state: fully visible tiles
+            tile_step(nq_c, body, std::integral_constant<int, 0>{}, tile);
+            issue(std::integral_constant<int, 0>{}, tile + PF);
+            if constexpr (PF > 1) {
+              tile_step(nq_c, body, std::integral_constant<int, 1>{}, tile + 1);
+              issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
+            }
+            if constexpr (PF > 2) {
+              tile_step(nq_c, body, std::integral_constant<int, 2>{}, tile + 2);
+              issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
+            }
+            if constexpr (PF > 3) {
+              tile_step(nq_c, body, std::integral_constant<int, 3>{}, tile + 3);
+              issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
+            }
+            tile += PF;
+          }
+          for (; tile < ring_end; tile += PF) {            // causal tail, and what is left over
+            tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
+            issue(std::integral_constant<int, 0>{}, tile + PF);
+            if constexpr (PF > 1) {
+              if (tile + 1 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, tile + 1);
+              issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
+            }
+            if constexpr (PF > 2) {
+              if (tile + 2 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 2>{}, tile + 2);
+              issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
+            }
+            if constexpr (PF > 3) {
+              if (tile + 3 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 3>{}, tile + 3);
+              issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
+            }
           }
         }
-
-        int tile = t_beg;
-        while (tile + PF <= fast_stop) {                 // steady state: fully visible tiles
-              tile_step(nq_c, body, std::integral_constant<int, 0>{}, tile);
-          issue(std::integral_constant<int, 0>{}, tile + PF);
-          if constexpr (PF > 1) {
-            tile_step(nq_c, body, std::integral_constant<int, 1>{}, tile + 1);
-            issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
-          }
-          if constexpr (PF > 2) {
-            tile_step(nq_c, body, std::integral_constant<int, 2>{}, tile + 2);
-            issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
-          }
-          if constexpr (PF > 3) {
-            tile_step(nq_c, body, std::integral_constant<int, 3>{}, tile + 3);
-            issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
-          }
-          tile += PF;
-        }
-        for (; tile < t_end; tile += PF) {               // causal tail, and what is left over
-              tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
-          issue(std::integral_constant<int, 0>{}, tile + PF);
-          if constexpr (PF > 1) {
-            if (tile + 1 < t_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, tile + 1);
-            issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
-          }
-          if constexpr (PF > 2) {
-            if (tile + 2 < t_end) tile_step(nq_c, tail, std::integral_constant<int, 2>{}, tile + 2);
-            issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
-          }
-          if constexpr (PF > 3) {
-            if (tile + 3 < t_end) tile_step(nq_c, tail, std::integral_constant<int, 3>{}, tile + 3);
-            issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
+        if constexpr (FRESH) {
+          for (int tile = fresh_beg; tile < t_end; ++tile) {   // the tiles with new tokens
+            load_fresh(tile);
+            if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0();
+            tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
           }
         }
 
@@ -586,10 +689,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ 
   *reinterpret_cast<bf16x4*>(out + ((int64_t)d.out_row + (int64_t)qi * H) * D + 4 * d4) = ob;
 }
 
-template <int D, int NQB, int PF, int WPS, bool PW>
-hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
-                      const BatchDev& b, float c, float inv_norm, void* workspace, hipStream_t stream) {
-  auto kern = attn_stream_kernel<D, NQB, PF, WPS, PW>;
+template <int D, int NQB, int PF, int WPS, bool PW, bool FRESH>
+hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, const uint16_t* k_new,
+                      const uint16_t* v_new, uint16_t* out, const BatchDev& b, float c, float inv_norm,
+                      void* workspace, hipStream_t stream) {
+  auto kern = attn_stream_kernel<D, NQB, PF, WPS, PW, FRESH>;
   const size_t lds_bytes = sizeof(int) * ((size_t)3 * b.batch + 2 + plan.n_items + 1 + kWavesPerWg);
   static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
   static size_t lds_limit = 48 * 1024;
@@ -615,7 +719,7 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
   MergeDesc* ws_desc = reinterpret_cast<MergeDesc*>(ws);
   float* ws_o = reinterpret_cast<float*>(ws + plan.ws_desc_bytes);
   float* ws_ml = ws_o + (int64_t)plan.max_waves * 2 * plan.q_tile * g.D;
-  hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, out, c, inv_norm, plan.q_tiles_max,
+  hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, k_new, v_new, out, c, inv_norm, plan.q_tiles_max,
                      plan.n_items, plan.min_tiles, ws_desc, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -628,9 +732,10 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
 // wavefront covers the first one's segment start-up and overlaps its VALU work with MFMA work.
 // D = 128: the accumulators and a useful ring need more than half the register file, so one
 // wavefront per SIMD with a deeper ring (3 tiles up to 32 queries per tile, else 2).
-template <int D, bool PW>
-hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, uint16_t* out,
-                    const BatchDev& b, float c, float inv_norm, void* ws, hipStream_t stream) {
+template <int D, bool PW, bool FRESH>
+hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, const uint16_t* k_new,
+                    const uint16_t* v_new, uint16_t* out, const BatchDev& b, float c, float inv_norm, void* ws,
+                    hipStream_t stream) {
 #ifndef MTS_PF_A
 #define MTS_PF_A 2   // D <= 64
 #define MTS_PF_B 3   // D = 128, up to 32 queries per tile
@@ -641,10 +746,10 @@ hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, 
   constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;
   constexpr int WPS = (D == 128) ? 1 : MTS_WPS_A;
   switch (plan.q_tile / 16) {
-    case 1: return launch_one<D, 1, PF_SMALL, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
-    case 2: return launch_one<D, 2, PF_SMALL, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
-    case 3: return launch_one<D, 3, PF_LARGE, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
-    default: return launch_one<D, 4, PF_LARGE, WPS, PW>(g, plan, q, out, b, c, inv_norm, ws, stream);
+    case 1: return launch_one<D, 1, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
+    case 2: return launch_one<D, 2, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
+    case 3: return launch_one<D, 3, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
+    default: return launch_one<D, 4, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
   }
 }
 
@@ -652,27 +757,29 @@ hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, 
 
 hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
                             const BatchDev& b, float sm_scale, float inv_norm, void* workspace,
-                            hipStream_t stream) {
+                            hipStream_t stream, const void* k_new, const void* v_new) {
   if (b.total_new <= 0 || b.batch <= 0) return hipSuccess;
-  if (inv_norm > 0.f) {                               // pointwise: the scale stays in natural units
-    const uint16_t* qp = reinterpret_cast<const uint16_t*>(q);
-    uint16_t* op = reinterpret_cast<uint16_t*>(out);
-    switch (g.D) {
-      case 32: return launch_d<32, true>(g, plan, qp, op, b, sm_scale, inv_norm, workspace, stream);
-      case 64: return launch_d<64, true>(g, plan, qp, op, b, sm_scale, inv_norm, workspace, stream);
-      case 128: return launch_d<128, true>(g, plan, qp, op, b, sm_scale, inv_norm, workspace, stream);
-      default: return hipErrorInvalidValue;
-    }
-  }
-  const float c = sm_scale * 1.4426950408889634f;     // logits are exponentiated in base 2
+  const bool pw = inv_norm > 0.f;
+  // pointwise: the scale stays in natural units; softmax: logits are exponentiated in base 2
+  const float c = pw ? sm_scale : sm_scale * 1.4426950408889634f;
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(q);
+  const uint16_t* kp = reinterpret_cast<const uint16_t*>(k_new);
+  const uint16_t* vp = reinterpret_cast<const uint16_t*>(v_new);
   uint16_t* op = reinterpret_cast<uint16_t*>(out);
+  const bool fresh = kp != nullptr;
+#define MTS_ATTN_CASE(D_)                                                                                        \
+  case D_:                                                                                                       \
+    if (pw) return fresh ? launch_d<D_, true, true>(g, plan, qp, kp, vp, op, b, c, inv_norm, workspace, stream)   \
+                         : launch_d<D_, true, false>(g, plan, qp, kp, vp, op, b, c, inv_norm, workspace, stream); \
+    return fresh ? launch_d<D_, false, true>(g, plan, qp, kp, vp, op, b, c, 0.f, workspace, stream)               \
+                 : launch_d<D_, false, false>(g, plan, qp, kp, vp, op, b, c, 0.f, workspace, stream);
   switch (g.D) {
-    case 32: return launch_d<32, false>(g, plan, qp, op, b, c, 0.f, workspace, stream);
-    case 64: return launch_d<64, false>(g, plan, qp, op, b, c, 0.f, workspace, stream);
-    case 128: return launch_d<128, false>(g, plan, qp, op, b, c, 0.f, workspace, stream);
+    MTS_ATTN_CASE(32)
+    MTS_ATTN_CASE(64)
+    MTS_ATTN_CASE(128)
     default: return hipErrorInvalidValue;
   }
+#undef MTS_ATTN_CASE
 }
 
 }  // namespace mts

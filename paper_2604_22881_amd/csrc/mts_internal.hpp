@@ -64,8 +64,10 @@ hipError_t launch_attn_generic(const PoolGeom& g, const void* q, void* out, cons
 bool attn_prefill_applicable(const PoolGeom& g, const BatchDev& b);
 hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
                                float sm_scale, float inv_norm, hipStream_t stream);
+// k_new / v_new non-NULL: this step's K/V rows ([token][H][D]) are read from there and the
+// pool's slots for them are not touched, so the layer's append need not have happened.
 hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
                             const BatchDev& b, float sm_scale, float inv_norm, void* workspace,
-                            hipStream_t stream);
+                            hipStream_t stream, const void* k_new = nullptr, const void* v_new = nullptr);
 
 }  // namespace mts

@@ -77,6 +77,24 @@ class GpuStep:
         torch.cuda.synchronize()
         return to_host(out[:w.total_new], w.np_dtype)
 
+    def attention_unappended(self, data, layer, sm_scale=0.0, inv_norm=None, append_stream=None):
+        """Attention with the step's K/V handed over as rows (no mts_kv_append before it); with
+        `append_stream`, the append runs on that stream at the same time."""
+        w = self.w
+        q, k, v = (to_dev(data[n][layer]) for n in ("q", "k_new", "v_new"))
+        out = torch.full((max(w.total_new, 1), w.heads, w.head_dim), -1, dtype=q.dtype, device=DEV)
+        torch.cuda.synchronize()
+        if append_stream is not None:
+            mts.mts_kv_append(self.cache.desc, layer, k, v, self.batch.meta, stream=append_stream)
+        if inv_norm is None:
+            mts.mts_attn_incremental_unappended(self.cache.desc, layer, q, k, v, out, self.batch.meta, sm_scale,
+                                                self.ws, self.ws_bytes)
+        else:
+            mts.mts_attn_pointwise_unappended(self.cache.desc, layer, q, k, v, out, self.batch.meta, inv_norm,
+                                              sm_scale, self.ws, self.ws_bytes)
+        torch.cuda.synchronize()
+        return to_host(out[:w.total_new], w.np_dtype)
+
     def pack(self, layer, users, positions, counts):
         w = self.w
         segs = SegmentList(users, positions, counts, DEV)
