@@ -43,6 +43,14 @@ def parse():
                          "\"serving_trace\" object to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
+    ap.add_argument("--append-first", action="store_true",
+                    help="diagnostic: Alg. 1's order layer by layer (mts_kv_append, then mts_attn_incremental "
+                         "reading the rows back from the pool) instead of the unappended attention with one "
+                         "append of all layers after the loop")
+    ap.add_argument("--restore-sync", choices=["step", "layer"], default="step",
+                    help="restored users' staged histories (already in HBM here): 'step' scatters all layers with "
+                         "one launch that layer 0 waits for; 'layer' scatters layer by layer with one event each "
+                         "(Alg. 1 step 8.3: what a restore arriving over PCIe needs, see --host-transfer)")
     ap.add_argument("--pack-per-layer", action="store_true",
                     help="diagnostic: gather layer l's evicted runs right after layer l's append, concurrently "
                          "with its attention, instead of after the layer loop")
@@ -388,16 +396,17 @@ def main():
     batch = DeviceBatch.from_workload(w, dev)
     N = w.total_new
     q = [torch.randn(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
-    k_new = [torch.randn(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
-    v_new = [torch.randn(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
+    k_new = torch.randn(L, N, H, D, device=dev, dtype=torch.bfloat16)     # one row buffer per layer
+    v_new = torch.randn(L, N, H, D, device=dev, dtype=torch.bfloat16)
     out = [torch.empty(N, H, D, device=dev, dtype=torch.bfloat16) for _ in range(L)]
     ws_bytes = mts.mts_attn_workspace_bytes(cache.desc, batch.meta)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
     miss = [] if args.no_miss else [int(u) for u in w.miss_users if w.prefix_lens[u] > 0]
     miss_segs = SegmentList.for_histories(miss, [w.prefix_lens[u] for u in miss], w.chunk_tokens, dev)
-    staging = [torch.randn(max(miss_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
-               for _ in range(L)]                        # onload buffer contents, one per layer
+    staging = torch.randn(L, max(miss_segs.total_tokens, 1) * 2 * H * D, device=dev,
+                          dtype=torch.bfloat16)          # onload buffer contents, one block per layer
+    staging_stride = staging.stride(0) * staging.element_size()
     evict = [] if args.no_evict else [int(u) for u in w.evict_users]
     evict_segs = SegmentList.for_histories(evict, [w.total_lens[u] for u in evict], w.chunk_tokens, dev)
     offload = torch.empty(L, max(evict_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
@@ -412,31 +421,53 @@ def main():
     pointwise = args.attention == "pointwise"
     inv_norm = 1.0 / max(1, int(w.total_lens.max()))
 
+    # Default: the attention takes the step's rows from k_new / v_new itself and every layer's rows are
+    # written to the pool by ONE launch after the layer loop (a serving engine keeps the L small row
+    # buffers of a step alive until then), so no copy sits between two layers' attentions.  Long new
+    # segments are appended by the unappended call itself.
+    deferred_append = not args.append_first and not mts.mts_attn_unappended_appends(cache.desc, batch.meta)
+    rows_stride = k_new.stride(0) * k_new.element_size()
+
     def step(attn_events=None):
-        for l in range(L):
-            if miss_segs.num_segs:
+        if miss_segs.num_segs and args.restore_sync == "layer":
+            for l in range(L):
                 mts.mts_kv_unpack(cache.desc, l, staging[l], *miss_segs.args(), batch.meta, stream=ss)
                 ev_unpacked[l].record(side)
+        elif miss_segs.num_segs:
+            mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride, *miss_segs.args(), batch.meta, stream=ss)
+            ev_unpacked[0].record(side)
         for l in range(L):
-            mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs)
-            ev_appended[l].record(compute)
-            if miss_segs.num_segs:
+            if args.append_first:
+                # Alg. 1's order: 8.2 append, then 8.4 attention reads the rows back from the pool
+                mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs)
+            if miss_segs.num_segs and (args.restore_sync == "layer" or l == 0):
                 compute.wait_event(ev_unpacked[l])
             if attn_events is not None:
                 a, b = attn_events[l]
                 a.record(compute)
-            if pointwise:
-                mts.mts_attn_pointwise(cache.desc, l, q[l], out[l], batch.meta, inv_norm, 0.0, ws, ws_bytes, stream=cs)
+            if args.append_first:
+                if pointwise:
+                    mts.mts_attn_pointwise(cache.desc, l, q[l], out[l], batch.meta, inv_norm, 0.0, ws, ws_bytes, stream=cs)
+                else:
+                    mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=cs)
+            elif pointwise:
+                mts.mts_attn_pointwise_unappended(cache.desc, l, q[l], k_new[l], v_new[l], out[l], batch.meta, inv_norm,
+                                                  0.0, ws, ws_bytes, stream=cs)
             else:
-                mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=cs)
+                mts.mts_attn_incremental_unappended(cache.desc, l, q[l], k_new[l], v_new[l], out[l], batch.meta, 0.0,
+                                                    ws, ws_bytes, stream=cs)
             if attn_events is not None:
                 b.record(compute)
-            if evict_segs.num_segs and args.pack_per_layer:
+            if evict_segs.num_segs and args.pack_per_layer and not deferred_append:
+                ev_appended[l].record(compute)
                 side.wait_event(ev_appended[l])
                 mts.mts_kv_pack(cache.desc, l, offload[l], *evict_segs.args(), batch.meta, stream=ss)
-        if evict_segs.num_segs and not args.pack_per_layer:
+        if deferred_append:
+            mts.mts_kv_append_layers(cache.desc, 0, L, k_new, v_new, rows_stride, batch.meta, stream=cs)
+        if evict_segs.num_segs and not (args.pack_per_layer and not deferred_append):
             # Alg. 1 step 9: the offload is submitted after the layer loop, behind the last append;
             # every layer's runs are gathered by one launch
+            ev_appended[L - 1].record(compute)
             side.wait_event(ev_appended[L - 1])
             mts.mts_kv_pack_layers(cache.desc, 0, L, offload, offload_stride, *evict_segs.args(), batch.meta, stream=ss)
 
@@ -499,6 +530,9 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic", "launch": "eager" if args.eager else "hip_graph",
+        "restore_sync": args.restore_sync,
+        "append": "per layer, before the attention" if args.append_first else
+                  ("all layers in one launch after the layer loop" if deferred_append else "inside the attention call"),
         "config": {"workload": w.name, "seed": w.seed, "users": w.batch, "layers": L, "heads": H,
                    "head_dim": D, "page_size": w.page_size, "prefix_tokens": int(w.prefix_lens.sum()),
                    "new_tokens": N, "miss_users": len(miss), "evict_users": len(evict),

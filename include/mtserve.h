@@ -166,6 +166,17 @@ int32_t mts_kv_pack_layers(const mts_cache_desc* cache, int32_t layer_begin, int
 int32_t mts_kv_append(const mts_cache_desc* cache, int32_t layer, const void* k_new,
                       const void* v_new, const mts_batch_meta* meta, void* stream);
 
+/*
+ * The same for `layer_count` consecutive layers in one launch: layer layer_begin + i takes its
+ * rows from k_new / v_new + i * rows_layer_stride_bytes (a multiple of 16).  For callers that
+ * keep every layer's rows until the end of the step - the attention calls that read them
+ * directly (mts_attn_*_unappended below) need no append in between - and then write all of
+ * them to the pool at once.  layer_count == 0 is a no-op.
+ */
+int32_t mts_kv_append_layers(const mts_cache_desc* cache, int32_t layer_begin, int32_t layer_count,
+                             const void* k_new, const void* v_new, int64_t rows_layer_stride_bytes,
+                             const mts_batch_meta* meta, void* stream);
+
 /* Workspace mts_attn_incremental needs for this cache and batch shape (host-only, >= 0;
  * < 0 on bad arguments).  The workspace is device memory, 256-byte aligned, and may be
  * reused by later calls on the same stream. */

@@ -20,7 +20,7 @@ MTS_F32, MTS_BF16 = 0, 1
 
 EXPORTS = (
     "mts_page_bytes", "mts_pages_for", "mts_elem_offset", "mts_kv_unpack", "mts_kv_pack",
-    "mts_kv_unpack_layers", "mts_kv_pack_layers",
+    "mts_kv_unpack_layers", "mts_kv_pack_layers", "mts_kv_append_layers",
     "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_pointwise",
     "mts_attn_unappended_appends", "mts_attn_incremental_unappended", "mts_attn_pointwise_unappended",
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
@@ -89,6 +89,7 @@ def lib():
         "mts_kv_unpack_layers": (I32, [DESC, I32, I32, P, I64, I32, P, P, P, I32, META, P]),
         "mts_kv_pack_layers": (I32, [DESC, I32, I32, P, I64, I32, P, P, P, I32, META, P]),
         "mts_kv_append": (I32, [DESC, I32, P, P, META, P]),
+        "mts_kv_append_layers": (I32, [DESC, I32, I32, P, P, I64, META, P]),
         "mts_attn_workspace_bytes": (I64, [DESC, META]),
         "mts_attn_incremental": (I32, [DESC, I32, P, P, META, F32, P, I64, P]),
         "mts_attn_pointwise": (I32, [DESC, I32, P, P, META, F32, F32, P, I64, P]),
@@ -210,6 +211,11 @@ def mts_kv_pack_layers(desc, layer_begin, layer_count, staging_out, staging_laye
 def mts_kv_append(desc, layer, k_new, v_new, meta, stream=None):
     return _check(lib().mts_kv_append(C.byref(desc), layer, _ptr(k_new), _ptr(v_new), C.byref(meta),
                                       _stream(stream)))
+
+
+def mts_kv_append_layers(desc, layer_begin, layer_count, k_new, v_new, rows_layer_stride_bytes, meta, stream=None):
+    return _check(lib().mts_kv_append_layers(C.byref(desc), layer_begin, layer_count, _ptr(k_new), _ptr(v_new),
+                                             int(rows_layer_stride_bytes), C.byref(meta), _stream(stream)))
 
 
 def mts_attn_incremental(desc, layer, q, out, meta, sm_scale=0.0, workspace=None, workspace_bytes=0,

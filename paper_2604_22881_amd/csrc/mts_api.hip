@@ -287,6 +287,27 @@ int32_t mts_kv_append(const mts_cache_desc* cache, int32_t layer, const void* k_
   return hip_status(mts::launch_append(g, k_new, v_new, b, static_cast<hipStream_t>(stream)), "mts_kv_append launch");
 }
 
+int32_t mts_kv_append_layers(const mts_cache_desc* cache, int32_t layer_begin, int32_t layer_count, const void* k_new,
+                             const void* v_new, int64_t rows_layer_stride_bytes, const mts_batch_meta* meta,
+                             void* stream) {
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  int32_t st;
+  if (layer_count < 0) return fail(MTS_ERR_INVALID_ARG, "layer_count is negative");
+  if ((st = check_cache(cache, layer_begin, true, &g)) != MTS_OK) return st;
+  if (layer_count > cache->num_layers - layer_begin)
+    return fail(MTS_ERR_INVALID_ARG, "layers [%d, %d) exceed the cache's %d layers", layer_begin,
+                layer_begin + layer_count, cache->num_layers);
+  if ((st = check_meta(meta, true, true, &b)) != MTS_OK) return st;
+  if (b.batch == 0 || b.total_new == 0 || layer_count == 0) return MTS_OK;
+  if (!k_new || !v_new) return fail(MTS_ERR_INVALID_ARG, "k_new / v_new is NULL");
+  if (!aligned(k_new, 16) || !aligned(v_new, 16) || (rows_layer_stride_bytes & 15) || rows_layer_stride_bytes < 0)
+    return fail(MTS_ERR_INVALID_ARG, "k_new / v_new and their layer stride must be multiples of 16 bytes");
+  return hip_status(mts::launch_append(g, k_new, v_new, b, static_cast<hipStream_t>(stream), layer_count,
+                                       cache->layer_stride_bytes, rows_layer_stride_bytes),
+                    "mts_kv_append_layers launch");
+}
+
 int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_meta* meta) {
   mts::PoolGeom g{};
   mts::BatchDev b{};

@@ -143,6 +143,9 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     const int n_u = s_tok[u + 1] - s_tok[u];
     if (q0 >= n_u) return 0;
     const int q1 = (n_u < q0 + QT) ? n_u : (q0 + QT);
+    // unappended: the cached prefix and the new rows are tiled separately (each from its own
+    // first token), so that no tile mixes the two sources
+    if (FRESH) return (s_P[u] + kTile - 1) / kTile + (q1 + kTile - 1) / kTile;
     return (s_P[u] + q1 + kTile - 1) / kTile;
   };
 
@@ -206,7 +209,9 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     const int q0 = (item % q_tiles_max) * QT;
     const int q1 = (n_u < q0 + QT) ? n_u : (q0 + QT);
     const int nq = q1 - q0;
-    const int tiles = (P + q1 + kTile - 1) / kTile;    // kv tiles of the whole (query tile, head)
+    const int pool_tiles = (P + kTile - 1) / kTile;    // unappended: tiles of the cached prefix
+    // kv tiles of the whole (query tile, head)
+    const int tiles = FRESH ? pool_tiles + (q1 + kTile - 1) / kTile : (P + q1 + kTile - 1) / kTile;
     const int item_pos = uniform(s_cum[item]);
     const int h = (pos - item_pos) / tiles;
     const int t_beg = (pos - item_pos) % tiles;
@@ -244,12 +249,16 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     // Page ids come through scalar loads (their counter is separate from the vector-memory
     // one, so they never force a wait on K/V data in flight).  Ring slot p keeps the ids of
     // the NEXT tile it will load, requested one ring revolution earlier.
-    // Unappended mode: the ring serves the tiles that lie in the pool entirely, [t_beg, ring_end);
-    // those with new tokens, [fresh_beg, t_end), follow one by one.
-    const int new_tile0 = P / kTile;                   // first tile that holds a new token
+    // Unappended mode: the ring serves the tiles of the cached prefix, [t_beg, ring_end); the
+    // tiles of new rows, [fresh_beg, t_end), follow one at a time.
     int ring_end = t_end;
-    if (FRESH && new_tile0 < ring_end) ring_end = new_tile0 > t_beg ? new_tile0 : t_beg;
+    if (FRESH && pool_tiles < ring_end) ring_end = pool_tiles > t_beg ? pool_tiles : t_beg;
     const int fresh_beg = FRESH ? ring_end : t_end;
+    // Which keys a query may see, as variables because the two kinds of tiles differ: a key at
+    // position kp is hidden from query block qb's lane r if kp > mask_q0 + mask_qstep * (16 qb + r);
+    // V slots at or past valid_end may hold anything and are cleared.  Tiles of the prefix in
+    // unappended mode: every query sees exactly the positions below P.
+    int mask_q0 = FRESH ? P - 1 : first_query_pos, mask_qstep = FRESH ? 0 : 1, valid_end = FRESH ? P : T_u;
     const int last_tile = ring_end - 1;
     int idr0[PF], idr1[PF];
     auto page_ids_at = [&](int tl, int& id0, int& id1) __attribute__((always_inline)) {
@@ -297,70 +306,49 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         vf[p][db] = *reinterpret_cast<const bf16x8*>(vl + db * 16 * 16 * 2);
       page_ids(tile + PF, idr0[p], idr1[p]);
     };
-    // ---- unappended mode: tiles that hold new tokens -------------------------------------
-    // Token position of the K row this lane loads for half-tile hf of a tile that starts at tb
-    // (the pool's slot order: see the K fragment above), and the address of that token's row in
-    // k_new if it is one of this step's tokens (positions past the user's last token repeat the
-    // last row: every query's mask hides them).
+    // ---- unappended mode: tiles of new rows ----------------------------------------------
+    // Tile ft holds the user's new tokens 32 ft .. 32 ft + 31 (positions P + ...), read from
+    // k_new / v_new through buffer descriptors that span exactly the user's rows of this head:
+    // tokens past the last one read as 0 without a branch.  A K fragment is one 16-byte load per
+    // lane (8 dims of the token's row), a V^T fragment one element from each of 8 rows.  All
+    // loads of a tile are in flight together; the ring has drained by then, so its registers
+    // are free.
+    const int row_bytes = H * D * 2;
+    __amdgpu_buffer_rsrc_t k_rows, v_rows;
+    if constexpr (FRESH) {
+      const int64_t first = ((int64_t)tok0 * H + h) * D;
+      const int span = (n_u - 1) * row_bytes + D * 2;
+      k_rows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(k_new + first), 0, span, 0x00020000);
+      v_rows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(v_new + first), 0, span, 0x00020000);
+    }
+    // the pool's slot order: token of the K row this lane holds in half-tile 0 (half-tile 1: + 4)
     const int k_lane_pos = ((r >> 3) << 4) + (((r & 7) >> 2) << 3) + (r & 3);
-    auto fresh_k_row = [&](int kp) __attribute__((always_inline)) -> const char* {
-      int idx = kp - P;
-      idx = idx < n_u - 1 ? idx : n_u - 1;
-      idx = idx > 0 ? idx : 0;
-      return reinterpret_cast<const char*>(k_new + ((int64_t)(tok0 + idx) * H + h) * D + 8 * gq);
-    };
-    // Loads tile `tile` (one with new tokens) into ring slot 0: lanes whose token is new read it
-    // from k_new / v_new, the others from the pool.  These few tiles per (query tile, head) are
-    // taken one at a time after the ring has drained, when its registers are free.
-    auto load_fresh = [&](int tile) __attribute__((always_inline)) {
-      const int tb = tile * kTile;
-      int id0, id1;
-      page_ids_at(tile, id0, id1);
-      const char *kb0, *kb1;
-      tile_bases_at(tile, id0, id1, kb0, kb1);
-      const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
+    auto load_fresh_k = [&](auto buf, int ft) __attribute__((always_inline)) {
+      constexpr int p = decltype(buf)::value;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        const int kp = tb + k_lane_pos + 4 * hf;
-        const char* row = fresh_k_row(kp);
+        int koff = (ft * kTile + k_lane_pos + 4 * hf) * row_bytes + 8 * gq * 2;
+        asm volatile("" : "+v"(koff));                 // computed here, not kept in a register across the ring
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          const char* src = (kp >= P) ? row + 32 * s * 2 : kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16;
-          kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(src);
-        }
+        for (int s = 0; s < KS; ++s)
+          kf[p][hf][s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(k_rows, koff + 32 * s * 2, 0, 0));
       }
-      // V^T: of this lane's 8 tokens, the first n_pool are cached ones (16 bytes from the pool,
-      // as always, masked to those tokens); the others come one element each from v_new through
-      // a buffer descriptor that spans exactly the user's new rows of this head, so that rows
-      // before the first and past the last new token read as 0 without a branch.  All loads are
-      // in flight together.
-      const char* vl = ((gq < 2) ? kb0 : kb1) + v_off + (r * 16 + (gq & 1) * 8) * 2;
-      const int vp = tb + 8 * gq;                      // first of this lane's 8 tokens
-      int n_pool = P - vp;
-      n_pool = n_pool < 0 ? 0 : (n_pool > 8 ? 8 : n_pool);
-      uint32_t pool_mask[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        pool_mask[j] = (2 * j < n_pool ? 0xffffu : 0u) | (2 * j + 1 < n_pool ? 0xffff0000u : 0u);
-        asm volatile("" : "+v"(pool_mask[j]));         // keeps the mask a mask (no branch per load)
-      }
-      const int row_bytes = H * D * 2;
-      const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<uint16_t*>(v_new + ((int64_t)tok0 * H + h) * D), 0, (n_u - 1) * row_bytes + D * 2, 0x00020000);
-      int idx0 = vp - P;                               // new-token index of the lane's first token
-      idx0 = idx0 > -8 ? idx0 : -8;                    // all 8 before the first new token: stays out of range
-      const int voff0 = idx0 * row_bytes + r * 2;
+    };
+    auto load_fresh = [&](auto buf, int ft) __attribute__((always_inline)) {
+      constexpr int p = decltype(buf)::value;
+      load_fresh_k(buf, ft);
+      int voff = (ft * kTile + 8 * gq) * row_bytes + r * 2;           // first of this lane's 8 tokens
+      asm volatile("" : "+v"(voff));                   // the 8 row offsets are formed per load, not hoisted
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const u32x4 pool = *reinterpret_cast<const u32x4*>(vl + db * 16 * 16 * 2);
         uint32_t f[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          f[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rows, voff0 + e * row_bytes + 32 * db, 0, 0);
+          f[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(v_rows, voff + e * row_bytes + 32 * db, 0, 0);
         u32x4 v;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (pool[j] & pool_mask[j]) | f[2 * j] | (f[2 * j + 1] << 16);
-        vf[0][db] = __builtin_bit_cast(bf16x8, v);
+        for (int j = 0; j < 4; ++j) v[j] = f[2 * j] | (f[2 * j + 1] << 16);
+        vf[p][db] = __builtin_bit_cast(bf16x8, v);
       }
     };
 
@@ -377,7 +365,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][1][s], qf[qb][s], s1, 0, 0, 0);
       }
       if (masked) {
-        const int qpos = first_query_pos + 16 * qb + r;
+        const int qpos = mask_q0 + mask_qstep * (16 * qb + r);
         const int kbase = tb + 8 * gq;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -396,20 +384,19 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     // softmax is shift-invariant, and weights above 1 are as exact in bf16 / fp32 as weights
     // below 1.  TAIL adds what only the causal tail needs: the mask, and zeroing of V slots past
     // the user's last token (they may hold anything).
-    auto tile_step = [&](auto nq_c, auto tail_c, auto buf, int tile) __attribute__((always_inline)) {
+    auto tile_step = [&](auto nq_c, auto tail_c, auto buf, int tb) __attribute__((always_inline)) {
       constexpr int NQ = decltype(nq_c)::value;
       constexpr bool TAIL = decltype(tail_c)::value;
-      constexpr int p = decltype(buf)::value;
-      const int tb = tile * kTile;
+      constexpr int p = decltype(buf)::value;      // tb: position of the tile's first token
       bool masked = false;
       if constexpr (TAIL) {
-        masked = (tb + kTile - 1 > first_query_pos);     // some key hidden from some query
-        if (masked && tb + kTile > T_u) {
+        masked = (tb + kTile - 1 > mask_q0);             // some key hidden from some query
+        if (masked && tb + kTile > valid_end) {
 #pragma unroll
           for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-              if (tb + 8 * gq + e >= T_u) vf[p][db][e] = (__bf16)0.0f;
+              if (tb + 8 * gq + e >= valid_end) vf[p][db][e] = (__bf16)0.0f;
         }
       }
 #pragma unroll
@@ -442,7 +429,8 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
       float mx[NQ];
 #pragma unroll
       for (int qb = 0; qb < NQ; ++qb) mx[qb] = -INFINITY;
-      for (int tile = t_beg; tile < t_end; ++tile) {
+      if constexpr (FRESH) { mask_q0 = P - 1; mask_qstep = 0; }
+      for (int tile = t_beg; tile < ring_end; ++tile) {
         int id0, id1;
         page_ids_at(tile, id0, id1);
         const char *kb0, *kb1;
@@ -450,21 +438,28 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
         const int tb = tile * kTile;
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-          const int kp = tb + k_lane_pos + 4 * hf;
-          const char* row = FRESH ? fresh_k_row(kp) : nullptr;
+        for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-          for (int s = 0; s < KS; ++s) {
-            const char* src = kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16;
-            if (FRESH && kp >= P) src = row + 32 * s * 2;
-            kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(src);
-          }
-        }
+          for (int s = 0; s < KS; ++s)
+            kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16);
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) {
           f32x4 s0, s1;
-          scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > first_query_pos, s0, s1);
+          scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > mask_q0, s0, s1);
           mx[qb] = fmaxf(mx[qb], max8(s0, s1));
+        }
+      }
+      if constexpr (FRESH) {
+        mask_q0 = first_query_pos; mask_qstep = 1;
+        for (int tile = fresh_beg; tile < t_end; ++tile) {
+          const int tb = P + (tile - pool_tiles) * kTile;
+          load_fresh_k(std::integral_constant<int, 0>{}, tile - pool_tiles);
+#pragma unroll
+          for (int qb = 0; qb < NQ; ++qb) {
+            f32x4 s0, s1;
+            scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > mask_q0, s0, s1);
+            mx[qb] = fmaxf(mx[qb], max8(s0, s1));
+          }
         }
       }
 #pragma unroll
@@ -475,7 +470,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     };
 
     // tiles [0, fast_stop) hide no key from any query of this tile
-    int fast_stop = (first_query_pos + 1) / kTile;
+    int fast_stop = FRESH ? P / kTile : (first_query_pos + 1) / kTile;
     if (fast_stop > ring_end) fast_stop = ring_end;
 
     // The whole segment for NQ query blocks.  Ring slots are integral_constants so that every
@@ -485,12 +480,11 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
       constexpr std::false_type body{};
       constexpr std::true_type tail{};
       // reference max = max of the segment's first tile (in ring slot 0 when this is called)
-      auto reference_from_slot0 = [&]() __attribute__((always_inline)) {
-        const int tb = t_beg * kTile;
+      auto reference_from_slot0 = [&](int tb) __attribute__((always_inline)) {
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) {
           f32x4 s0, s1;
-          scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > first_query_pos, s0, s1);
+          scores(std::integral_constant<int, 0>{}, qb, tb, tb + kTile - 1 > mask_q0, s0, s1);
           m[qb] = quad_row_max(max8(s0, s1));
           mcq[qb] = (m[qb] == -INFINITY ? 0.f : m[qb]) * c;    // nothing visible: any reference
         }
@@ -506,6 +500,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
           if (attempt == 1) exact_max(nq_c);
         }
 
+        if constexpr (FRESH) { mask_q0 = P - 1; mask_qstep = 0; valid_end = P; }
         if (!FRESH || ring_end > t_beg) {
           page_ids(t_beg, idr0[0], idr1[0]);
           if constexpr (PF > 1) page_ids(t_beg + 1, idr0[1], idr1[1]);
@@ -516,48 +511,50 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
           if constexpr (PF > 2) issue(std::integral_constant<int, 2>{}, t_beg + 2);
           if constexpr (PF > 3) issue(std::integral_constant<int, 3>{}, t_beg + 3);
 
-          if (!PW && attempt == 0) reference_from_slot0();
+          if (!PW && attempt == 0) reference_from_slot0(t_beg * kTile);
 
           int tile = t_beg;
           while (tile + PF <= fast_stop) {                 // steady state: fully visible tiles
-            tile_step(nq_c, body, std::integral_constant<int, 0>{}, tile);
+            tile_step(nq_c, body, std::integral_constant<int, 0>{}, (tile) * kTile);
             issue(std::integral_constant<int, 0>{}, tile + PF);
             if constexpr (PF > 1) {
-              tile_step(nq_c, body, std::integral_constant<int, 1>{}, tile + 1);
+              tile_step(nq_c, body, std::integral_constant<int, 1>{}, (tile + 1) * kTile);
               issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
             }
             if constexpr (PF > 2) {
-              tile_step(nq_c, body, std::integral_constant<int, 2>{}, tile + 2);
+              tile_step(nq_c, body, std::integral_constant<int, 2>{}, (tile + 2) * kTile);
               issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
             }
             if constexpr (PF > 3) {
-              tile_step(nq_c, body, std::integral_constant<int, 3>{}, tile + 3);
+              tile_step(nq_c, body, std::integral_constant<int, 3>{}, (tile + 3) * kTile);
               issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
             }
             tile += PF;
           }
           for (; tile < ring_end; tile += PF) {            // causal tail, and what is left over
-            tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
+            tile_step(nq_c, tail, std::integral_constant<int, 0>{}, (tile) * kTile);
             issue(std::integral_constant<int, 0>{}, tile + PF);
             if constexpr (PF > 1) {
-              if (tile + 1 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, tile + 1);
+              if (tile + 1 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, (tile + 1) * kTile);
               issue(std::integral_constant<int, 1>{}, tile + 1 + PF);
             }
             if constexpr (PF > 2) {
-              if (tile + 2 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 2>{}, tile + 2);
+              if (tile + 2 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 2>{}, (tile + 2) * kTile);
               issue(std::integral_constant<int, 2>{}, tile + 2 + PF);
             }
             if constexpr (PF > 3) {
-              if (tile + 3 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 3>{}, tile + 3);
+              if (tile + 3 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 3>{}, (tile + 3) * kTile);
               issue(std::integral_constant<int, 3>{}, tile + 3 + PF);
             }
           }
         }
         if constexpr (FRESH) {
-          for (int tile = fresh_beg; tile < t_end; ++tile) {   // the tiles with new tokens
-            load_fresh(tile);
-            if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0();
-            tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile);
+          mask_q0 = first_query_pos; mask_qstep = 1; valid_end = T_u;
+          for (int tile = fresh_beg; tile < t_end; ++tile) {      // the tiles of new rows
+            const int ft = tile - pool_tiles;
+            load_fresh(std::integral_constant<int, 0>{}, ft);
+            if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0(P + ft * kTile);
+            tile_step(nq_c, tail, std::integral_constant<int, 0>{}, P + ft * kTile);
           }
         }
 

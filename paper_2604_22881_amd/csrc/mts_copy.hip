@@ -48,9 +48,10 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
   constexpr int dch = DCH;
   const int HC = H * dch;
   const int s = blockIdx.y;
-  // several layers in one launch (unpack / pack): blockIdx.z picks the layer on both sides
+  // several layers in one launch: blockIdx.z picks the layer on both sides
   g.layer_base += (int64_t)blockIdx.z * pool_layer_stride;
   src_a += (int64_t)blockIdx.z * contig_layer_stride;
+  if (MODE == MODE_APPEND) src_b += (int64_t)blockIdx.z * contig_layer_stride;
   if (MODE == MODE_PACK) dst_contig += (int64_t)blockIdx.z * contig_layer_stride;
 
   // Resolve the run: user, first pool token, length, and the contiguous K / V planes.  The
@@ -359,10 +360,11 @@ hipError_t launch_pack(const PoolGeom& g, void* staging_out, const SegDev& segs,
                                 staging_out, stream, layers, pool_layer_stride, staging_layer_stride);
 }
 
-hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new,
-                         const BatchDev& b, hipStream_t stream) {
+hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new, const BatchDev& b,
+                         hipStream_t stream, int layers, int64_t pool_layer_stride, int64_t rows_layer_stride) {
   SegDev none{};
-  return launch_move<MODE_APPEND>(g, none, b, b.batch, b.max_new, k_new, v_new, nullptr, stream);
+  return launch_move<MODE_APPEND>(g, none, b, b.batch, b.max_new, k_new, v_new, nullptr, stream, layers,
+                                  pool_layer_stride, rows_layer_stride);
 }
 
 }  // namespace mts

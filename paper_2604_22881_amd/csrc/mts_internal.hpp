@@ -39,8 +39,9 @@ hipError_t launch_unpack(const PoolGeom& g, const void* staging, const SegDev& s
 hipError_t launch_pack(const PoolGeom& g, void* staging_out, const SegDev& segs, const BatchDev& b,
                        hipStream_t stream, int layers = 1, int64_t pool_layer_stride = 0,
                        int64_t staging_layer_stride = 0);
-hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new,
-                         const BatchDev& b, hipStream_t stream);
+hipError_t launch_append(const PoolGeom& g, const void* k_new, const void* v_new, const BatchDev& b,
+                         hipStream_t stream, int layers = 1, int64_t pool_layer_stride = 0,
+                         int64_t rows_layer_stride = 0);
 
 // Shape plan of one attention call: computed on the host from the scalar bounds only.
 struct AttnPlan {

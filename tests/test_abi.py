@@ -169,6 +169,32 @@ def test_bad_layer_ranges_are_rejected():
         assert fn(d, 0, 2, None, 0, 0, None, None, None, 0, m, stream=0) == 0
 
 
+def test_bad_append_layers_arguments_are_rejected():
+    d, m = _desc(), _meta()          # the descriptor has 2 layers
+    fn = mts.mts_kv_append_layers
+    assert _code(fn, d, 0, 3, FAKE, FAKE, 4096, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 1, 2, FAKE, FAKE, 4096, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, -1, FAKE, FAKE, 4096, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, 2, None, FAKE, 4096, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, 2, FAKE, FAKE + 4, 4096, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, 2, FAKE, FAKE, 4100, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert fn(d, 0, 0, None, None, 0, m, stream=0) == 0
+    assert fn(d, 0, 2, None, None, 0, _meta(total_new=0, max_new=0), stream=0) == 0
+
+
+def test_unappended_attention_arguments():
+    d, m = _desc(), _meta()
+    fn = mts.mts_attn_incremental_unappended
+    assert _code(fn, d, 0, FAKE, None, FAKE, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, FAKE, FAKE, FAKE + 2, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(mts.mts_attn_pointwise_unappended, d, 0, FAKE, FAKE, FAKE, FAKE, m, 0.0, stream=0) == B.MTS_ERR_INVALID_ARG
+    # which shapes the unappended calls append by themselves: fp32 caches and long new segments
+    assert mts.mts_attn_unappended_appends(d, m) is False
+    assert mts.mts_attn_unappended_appends(_desc(dtype=B.MTS_F32), m) is True
+    long_new = _meta(batch=2, total_new=1024, max_new=512, max_total_len=600, total_pages=8)
+    assert mts.mts_attn_unappended_appends(d, long_new) is True
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -419,3 +419,33 @@ def test_several_layers_in_one_launch(dtype, D, S):
         assert b"".join(g.tobytes() for g in single) == flat[i * pstride:i * pstride + psegs.total_tokens * row].tobytes()
     for l in range(L):
         assert np.array_equal(step.pool_image(l), G.expected_pool_image(w, store, l, FILL)), f"layer {l} after pack"
+
+
+@pytest.mark.parametrize("dtype,D,S", [("bf16", 64, 16), ("f32", 32, 32), ("bf16", 128, 64)])
+def test_append_several_layers_in_one_launch(dtype, D, S):
+    """mts_kv_append_layers on a range of layers inside a larger cache (row buffers a padded
+    stride apart): those layers hold exactly what the oracle's append wrote after the histories,
+    the others are untouched."""
+    import torch
+    import paper_2604_22881_amd as mts
+    G = _harness()
+    L, lo, cnt_l = 4, 1, 3
+    prefix, new = [300, 17, 0, 129, 640], [5, 0, 40, 3, 200]
+    w = W.custom_workload("append_layers", 4243, dtype, L, 3, D, S, prefix, new, chunk_tokens=200)
+    data = draw_step_data(w, layers=range(lo, lo + cnt_l))
+    step = G.GpuStep(w, fill_byte=FILL)
+    for l in range(lo, lo + cnt_l):
+        step.unpack_histories(data, l)
+    n = w.total_new * w.heads * D
+    stride = n + 40                                           # elements; 80 or 160 bytes of padding
+    k = np.zeros(cnt_l * stride, dtype=w.np_dtype)
+    v = np.zeros(cnt_l * stride, dtype=w.np_dtype)
+    for i in range(cnt_l):
+        k[i * stride:i * stride + n] = np.ascontiguousarray(data["k_new"][lo + i]).reshape(-1)
+        v[i * stride:i * stride + n] = np.ascontiguousarray(data["v_new"][lo + i]).reshape(-1)
+    mts.mts_kv_append_layers(step.cache.desc, lo, cnt_l, G.to_dev(k), G.to_dev(v), stride * w.elem_bytes,
+                             step.batch.meta)
+    torch.cuda.synchronize()
+    store = _oracle_store(w, data, do_append=True)
+    for l in range(L):
+        assert np.array_equal(step.pool_image(l), G.expected_pool_image(w, store, l, FILL)), f"layer {l}"
