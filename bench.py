@@ -3,11 +3,15 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
-A step is one pass of the whole hot path over one batch of the synthetic workload: per layer
-mts_kv_append then mts_attn_incremental on the compute stream, while a side stream restores
-the batch's cache-miss users from an HBM-resident staging buffer (mts_kv_unpack, one event per
-layer that the layer's attention waits for, as in Alg. 1 step 8.3) and, after the layer loop,
-packs the users chosen for offload (mts_kv_pack, Alg. 1 step 9).  All inputs are resident in HBM before the timed region.
+A step is one pass of the whole hot path over one batch of the synthetic workload: the batch's
+cache-miss users are restored from an HBM-resident staging buffer (mts_kv_unpack_layers), every
+layer runs its attention over the cached prefix plus the step's own K/V rows
+(mts_attn_incremental_unappended), the rows of all layers are then written to the pool
+(mts_kv_append_layers, Alg. 1 step 8.2 deferred to the end of the loop) and the users chosen for
+offload are gathered (mts_kv_pack_layers, Alg. 1 step 9).  --append-first and --restore-sync layer
+select Alg. 1's literal order and stream structure instead (append before each layer's attention;
+scatter on a side stream with one event per layer, step 8.3).  All inputs are resident in HBM
+before the timed region.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -49,8 +53,9 @@ def parse():
                          "append of all layers after the loop")
     ap.add_argument("--restore-sync", choices=["step", "layer"], default="step",
                     help="restored users' staged histories (already in HBM here): 'step' scatters all layers with "
-                         "one launch that layer 0 waits for; 'layer' scatters layer by layer with one event each "
-                         "(Alg. 1 step 8.3: what a restore arriving over PCIe needs, see --host-transfer)")
+                         "one launch ahead of layer 0 and gathers the offload after the appends, all on one stream; "
+                         "'layer' scatters on a side stream layer by layer with one event each and gathers there "
+                         "too (Alg. 1 steps 8.3 and 9: what a restore arriving over PCIe needs, see --host-transfer)")
     ap.add_argument("--pack-per-layer", action="store_true",
                     help="diagnostic: gather layer l's evicted runs right after layer l's append, concurrently "
                          "with its attention, instead of after the layer loop")
@@ -428,19 +433,26 @@ def main():
     deferred_append = not args.append_first and not mts.mts_attn_unappended_appends(cache.desc, batch.meta)
     rows_stride = k_new.stride(0) * k_new.element_size()
 
+    # 'layer': the paper's stream structure - scatter on the side stream with one event per layer that
+    # the layer's attention waits for (Alg. 1 step 8.3), offload gathered on the side stream behind the
+    # appends (step 9).  'step': the staged histories are already in HBM, so nothing is gained by
+    # pipelining them layer by layer; scatter, attention, append and gather follow one another on one
+    # stream and no cross-stream dependency (several microseconds each) sits between two layers.
+    per_layer = args.restore_sync == "layer"
+    xs = ss if per_layer else cs                          # stream of the scatter and the gather
+
     def step(attn_events=None):
-        if miss_segs.num_segs and args.restore_sync == "layer":
+        if miss_segs.num_segs and per_layer:
             for l in range(L):
                 mts.mts_kv_unpack(cache.desc, l, staging[l], *miss_segs.args(), batch.meta, stream=ss)
                 ev_unpacked[l].record(side)
         elif miss_segs.num_segs:
-            mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride, *miss_segs.args(), batch.meta, stream=ss)
-            ev_unpacked[0].record(side)
+            mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride, *miss_segs.args(), batch.meta, stream=cs)
         for l in range(L):
             if args.append_first:
                 # Alg. 1's order: 8.2 append, then 8.4 attention reads the rows back from the pool
                 mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs)
-            if miss_segs.num_segs and (args.restore_sync == "layer" or l == 0):
+            if miss_segs.num_segs and per_layer:
                 compute.wait_event(ev_unpacked[l])
             if attn_events is not None:
                 a, b = attn_events[l]
@@ -467,9 +479,10 @@ def main():
         if evict_segs.num_segs and not (args.pack_per_layer and not deferred_append):
             # Alg. 1 step 9: the offload is submitted after the layer loop, behind the last append;
             # every layer's runs are gathered by one launch
-            ev_appended[L - 1].record(compute)
-            side.wait_event(ev_appended[L - 1])
-            mts.mts_kv_pack_layers(cache.desc, 0, L, offload, offload_stride, *evict_segs.args(), batch.meta, stream=ss)
+            if per_layer:
+                ev_appended[L - 1].record(compute)
+                side.wait_event(ev_appended[L - 1])
+            mts.mts_kv_pack_layers(cache.desc, 0, L, offload, offload_stride, *evict_segs.args(), batch.meta, stream=xs)
 
     for _ in range(args.warmup):
         step()

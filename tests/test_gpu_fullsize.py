@@ -5,6 +5,8 @@ checked (a) element by element on sampled (user, head) pairs whose K/V/Q are see
 staged through mts_kv_unpack / mts_kv_append, and (b) on every output row through a property
 that holds at any size: with all values equal to one, every output element is exactly one
 (softmax weights sum to one; numerator and denominator see the same rounded weights).
+Both orders that bench.py can time are covered: append then attention from the pool, and the
+attention that takes the step's rows directly followed by the deferred append.
 """
 import dataclasses
 
@@ -36,9 +38,10 @@ def _sample_users(w, rng, count):
     return sorted(picks)
 
 
+@pytest.mark.parametrize("unappended", [False, True])
 @pytest.mark.parametrize("name,n_users,n_heads", [("batched_incremental", 8, 3), ("long_history", 4, 2),
                                                   ("host_staging", 6, 2), ("miss_prefill", 2, 2)])
-def test_sampled_pairs_match_oracle(name, n_users, n_heads):
+def test_sampled_pairs_match_oracle(name, n_users, n_heads, unappended):
     torch, G, w, step = _setup(name)
     rng = np.random.default_rng([w.seed, 5])
     users = _sample_users(w, rng, n_users)
@@ -53,8 +56,15 @@ def test_sampled_pairs_match_oracle(name, n_users, n_heads):
     data["v_new"] = {0: W.normal_elements(rng, (w.total_new, H, D), w.dtype)}
     data["q"] = {0: W.normal_elements(rng, (w.total_new, H, D), w.dtype)}
     step.unpack_histories(data, 0, users=users)
-    step.append(data, 0)
-    got = step.attention(data, 0)
+    if unappended:
+        import paper_2604_22881_amd as mts
+        got = step.attention_unappended(data, 0)
+        k, v = G.to_dev(data["k_new"][0]), G.to_dev(data["v_new"][0])
+        mts.mts_kv_append_layers(step.cache.desc, 0, 1, k, v, k.numel() * k.element_size(), step.batch.meta)
+        torch.cuda.synchronize()
+    else:
+        step.append(data, 0)
+        got = step.attention(data, 0)
     for u in users:
         pages = w.user_pages(u)
         for start, cnt in W.host_chunks(int(w.prefix_lens[u]), w.chunk_tokens):
@@ -82,8 +92,9 @@ def test_sampled_pairs_match_oracle(name, n_users, n_heads):
     assert packed.tobytes() == oracle.pack(store, 0, w.user_pages(u), 0, T).tobytes()
 
 
+@pytest.mark.parametrize("unappended", [False, True])
 @pytest.mark.parametrize("name", ["batched_incremental", "long_history", "host_staging", "miss_prefill"])
-def test_unit_values_give_unit_output_everywhere(name):
+def test_unit_values_give_unit_output_everywhere(name, unappended):
     torch, G, w, step = _setup(name)
     H, D, S = w.heads, w.head_dim, w.page_size
     # every V block of the pool := 1.0 (head block = K block then V block, S*D elements each)
@@ -92,6 +103,12 @@ def test_unit_values_give_unit_output_everywhere(name):
     q = torch.randn(w.total_new, H, D, device=G.DEV, dtype=torch.bfloat16)
     out = torch.zeros_like(q)
     import paper_2604_22881_amd as mts
-    mts.mts_attn_incremental(step.cache.desc, 0, q, out, step.batch.meta, 0.0, step.ws, step.ws_bytes)
+    if unappended:
+        # the step's value rows are ones as well; its key rows are random like the pool's
+        k_new, v_new = torch.randn_like(q), torch.ones_like(q)
+        mts.mts_attn_incremental_unappended(step.cache.desc, 0, q, k_new, v_new, out, step.batch.meta, 0.0,
+                                            step.ws, step.ws_bytes)
+    else:
+        mts.mts_attn_incremental(step.cache.desc, 0, q, out, step.batch.meta, 0.0, step.ws, step.ws_bytes)
     torch.cuda.synchronize()
     assert bool((out == 1.0).all()), f"{name}: {(out != 1.0).sum().item()} of {out.numel()} elements differ from 1"
