@@ -429,8 +429,9 @@ def main():
     # Default: the attention takes the step's rows from k_new / v_new itself and every layer's rows are
     # written to the pool by ONE launch after the layer loop (a serving engine keeps the L small row
     # buffers of a step alive until then), so no copy sits between two layers' attentions.  Long new
-    # segments are appended by the unappended call itself.
+    # segments (read from the pool by the dense-prefill kernel) keep Alg. 1's order: append, then attention.
     deferred_append = not args.append_first and not mts.mts_attn_unappended_appends(cache.desc, batch.meta)
+    append_first = not deferred_append                    # such shapes take Alg. 1's order, call by call
     rows_stride = k_new.stride(0) * k_new.element_size()
 
     # 'layer': the paper's stream structure - scatter on the side stream with one event per layer that
@@ -449,7 +450,7 @@ def main():
         elif miss_segs.num_segs:
             mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride, *miss_segs.args(), batch.meta, stream=cs)
         for l in range(L):
-            if args.append_first:
+            if append_first:
                 # Alg. 1's order: 8.2 append, then 8.4 attention reads the rows back from the pool
                 mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs)
             if miss_segs.num_segs and per_layer:
@@ -457,7 +458,7 @@ def main():
             if attn_events is not None:
                 a, b = attn_events[l]
                 a.record(compute)
-            if args.append_first:
+            if append_first:
                 if pointwise:
                     mts.mts_attn_pointwise(cache.desc, l, q[l], out[l], batch.meta, inv_norm, 0.0, ws, ws_bytes, stream=cs)
                 else:
@@ -544,8 +545,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic", "launch": "eager" if args.eager else "hip_graph",
         "restore_sync": args.restore_sync,
-        "append": "per layer, before the attention" if args.append_first else
-                  ("all layers in one launch after the layer loop" if deferred_append else "inside the attention call"),
+        "append": "all layers in one launch after the layer loop" if deferred_append else "per layer, before the attention",
         "config": {"workload": w.name, "seed": w.seed, "users": w.batch, "layers": L, "heads": H,
                    "head_dim": D, "page_size": w.page_size, "prefix_tokens": int(w.prefix_lens.sum()),
                    "new_tokens": N, "miss_users": len(miss), "evict_users": len(evict),
@@ -554,7 +554,7 @@ def main():
         "kv_read_frac_of_peak_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "attention_tflops": flops / (attn_ms_avg * 1e-3) / 1e12,
         "roofline": {"kernel": ("mts_attn_pointwise" if pointwise else "mts_attn_incremental") +
-                               " (attention kernel + split-kv merge)",
+                               ("_unappended" if deferred_append else "") + " (attention kernel + split-kv merge)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "bytes_per_launch": alg_bytes, "avg_launch_ms": attn_ms_avg},
