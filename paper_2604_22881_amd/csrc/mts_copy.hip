@@ -5,16 +5,12 @@
 //
 // All three are HBM-bound permutations of 16-byte granules (K) and of elements (V, whose pool
 // layout is [dim][token]); see kv_move_kernel for how the work is split.
+#include <type_traits>
+
 #include "mts_internal.hpp"
 
 namespace mts {
 namespace {
-
-template <typename T>
-union Granule {
-  uint4 v;
-  T     e[16 / sizeof(T)];
-};
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));          // one granule, opaque
 template <typename T> struct ElemVec;                                // one granule, as elements
@@ -25,15 +21,16 @@ enum { MODE_UNPACK = 0, MODE_APPEND = 1, MODE_PACK = 2 };
 
 constexpr int kBulkWaves = 4;      // wavefronts (= units) per bulk workgroup
 
-// One launch serves both kinds of work.  Workgroups [0, bulk_blocks) take the 16-token
-// sub-blocks that a run covers completely, one wavefront per (sub-block, head): the
-// contiguous side moves in whole rows (D*es bytes per token and head), the pool side in whole
-// 16-byte granules in pool order, so that BOTH sides of every copy are 16-byte-per-lane
-// accesses over full cache lines; the reordering in between - the K granule permutation and
-// the V transpose - goes through a wavefront-private LDS tile of 16 rows (padded by one
-// granule, which keeps the strided accesses off a single bank).  Workgroups behind them take
-// the token groups of partly covered sub-blocks at the two ends of a run, element-wise on the
-// pool side: no slot outside the run is ever written.
+// One wavefront moves one (16-token sub-block, head): the contiguous side moves in whole rows
+// (D*es bytes per token and head), the pool side in whole 16-byte granules in pool order, so that
+// BOTH sides of every copy are 16-byte-per-lane accesses over full cache lines; the reordering
+// in between - the K granule permutation and the V transpose - goes through a wavefront-private
+// LDS tile of 16 rows (padded by one granule, which keeps the strided accesses off a single
+// bank).  Workgroups [0, bulk_blocks) take the sub-blocks that a run covers completely; those
+// behind them take partly covered sub-blocks with the same code under a token mask: rows outside
+// the run are neither read nor written, K granules of other tokens are skipped and a V granule
+// that the run covers only in part is written element by element, so no slot outside the run
+// is ever written.
 template <typename T, int MODE, int DCH>
 __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, BatchDev b,
                                                       const T* __restrict__ src_a,
@@ -46,7 +43,6 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
   constexpr int NIT = 16 * DCH / 64; // 64-granule rounds per 16-token sub-block
   const int H = g.H, S = g.S;
   constexpr int dch = DCH;
-  const int HC = H * dch;
   const int s = blockIdx.y;
   // several layers in one launch: blockIdx.z picks the layer on both sides
   g.layer_base += (int64_t)blockIdx.z * pool_layer_stride;
@@ -98,15 +94,46 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
   int64_t full_hi = (ppos + npos) >> 4;
   if (full_hi < full_lo || bulk_blocks == 0) full_hi = full_lo;   // short runs: everything goes group by group
 
+  // Which sub-block this wavefront moves, and which of its 16 tokens belong to the run.
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t first_sb = ppos >> 4, last_sb = (ppos + npos - 1) >> 4;
+  int64_t sb;
+  int h;
+  bool masked;
   if ((int)blockIdx.x < bulk_blocks) {
-    // ---------------- whole sub-blocks: one wavefront per (sub-block, head) ----------------
-    __shared__ __attribute__((aligned(16))) T tile[kBulkWaves][16 * PITCH];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // whole sub-blocks: one wavefront per (sub-block, head)
     const int64_t unit = (int64_t)blockIdx.x * kBulkWaves + wave;
-    const int64_t sb = full_lo + unit / H;
-    const int h = (int)(unit % H);
+    sb = full_lo + unit / H;
+    h = (int)(unit % H);
+    masked = false;
     if (!run_ok || sb >= full_hi) return;                       // wavefront-uniform; no block barrier below
-    const int64_t lp = (sb << 4) / S;
+  } else {
+    // the sub-blocks the whole-sub-block part leaves: all of a run's when the launch has no such
+    // part (unit k = k-th sub-block of the run), else the partly covered ones at its two ends
+    const int64_t unit = (int64_t)(blockIdx.x - bulk_blocks) * kBulkWaves + wave;
+    const int64_t k = unit / H;
+    h = (int)(unit % H);
+    masked = true;
+    if (bulk_blocks == 0) {
+      sb = first_sb + k;
+    } else {
+      const bool head_part = first_sb < full_lo;                            // unit 0: partly covered first
+      const bool tail_part = last_sb >= full_hi && !(head_part && last_sb == first_sb);   // unit 1: last
+      sb = (k == 0 && head_part) ? first_sb : ((k == 1 && tail_part) ? last_sb : -1);
+    }
+    if (!run_ok || sb < 0 || sb > last_sb) return;
+  }
+  const int64_t sbase = sb << 4;
+  int t_lo = 0, t_hi = 16;                                      // tokens of the sub-block inside the run
+  if (masked) {
+    t_lo = (int)(ppos > sbase ? ppos - sbase : 0);
+    t_hi = (int)(ppos + npos < sbase + 16 ? ppos + npos - sbase : 16);
+  }
+  __shared__ __attribute__((aligned(16))) T tile[kBulkWaves][16 * PITCH];
+  // masked_c: compile-time copy of `masked`, so that the whole-sub-block form carries no checks
+  auto move_sub_block = [&](auto masked_c) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;
+    const int64_t lp = sbase / S;
     if (lp >= npg) return;
     const int page = b.page_indices[pbeg + lp];
     if ((unsigned)page >= (unsigned)g.num_pages) return;
@@ -114,14 +141,16 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
     char* head = g.layer_base + (int64_t)page * g.page_bytes;
     T* kblk = reinterpret_cast<T*>(head + head_block_offset(0, h, S, D, sizeof(T))) + (int64_t)sub * 16 * D;
     T* vblk = reinterpret_cast<T*>(head + head_block_offset(1, h, S, D, sizeof(T))) + (int64_t)sub * 16 * D;
-    const int64_t row0 = (sb << 4) - ppos;                      // contiguous-side row of the sub-block's token 0
+    const int64_t row0 = sbase - ppos;                          // contiguous-side row of the sub-block's token 0
     T* lt = tile[wave];                                         // [16 tokens][PITCH]: K first, then V
     // LDS operations of one wavefront execute in order; the fence only pins the compiler's order
     auto wave_sync = [] {
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
     };
+    auto in_run = [&](int t) { return !MASKED || (t >= t_lo && t < t_hi); };
     typedef typename ElemVec<T>::type EV;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
     u32x4 kg[NIT], vg[NIT];
     if (MODE != MODE_PACK) {
       // rows in (whole D*es-byte runs), granules out in pool order
@@ -129,8 +158,9 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
       for (int j = 0; j < NIT; ++j) {
         const int gi = j * 64 + lane, t = gi / dch, c = gi % dch;
         const int64_t off = (row0 + t) * H * D + (int64_t)h * D + c * G;
-        kg[j] = *reinterpret_cast<const u32x4*>(k_plane + off);
-        vg[j] = *reinterpret_cast<const u32x4*>(v_plane + off);
+        const bool ok = in_run(t);
+        kg[j] = ok ? *reinterpret_cast<const u32x4*>(k_plane + (ok ? off : 0)) : zero;
+        vg[j] = ok ? *reinterpret_cast<const u32x4*>(v_plane + (ok ? off : 0)) : zero;
       }
 #pragma unroll
       for (int j = 0; j < NIT; ++j) {
@@ -164,8 +194,23 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
 #pragma unroll
       for (int j = 0; j < NIT; ++j) {
         const int p = j * 64 + lane;
-        *reinterpret_cast<u32x4*>(kblk + (int64_t)p * G) = kg[j];
-        *reinterpret_cast<u32x4*>(vblk + (int64_t)p * G) = vg[j];
+        const int slot = p % 8, half = p / (dch * 8);
+        const int t = ((slot >> 2) << 3) + half * 4 + (slot & 3);         // token of K granule p
+        if (in_run(t)) *reinterpret_cast<u32x4*>(kblk + (int64_t)p * G) = kg[j];
+        // V granule p holds tokens part*G .. part*G+G-1 of one dim: whole if the run covers all
+        // of them, else element by element - no slot outside the run is written
+        const int part = p % (16 / G);
+        int e_lo = t_lo - part * G, e_hi = t_hi - part * G;
+        e_lo = e_lo < 0 ? 0 : e_lo;
+        e_hi = e_hi > G ? G : e_hi;
+        if (!MASKED || (e_lo == 0 && e_hi == G)) {
+          *reinterpret_cast<u32x4*>(vblk + (int64_t)p * G) = vg[j];
+        } else if (e_lo < e_hi) {
+          const EV o = __builtin_bit_cast(EV, vg[j]);
+#pragma unroll
+          for (int e = 0; e < G; ++e)
+            if (e >= e_lo && e < e_hi) vblk[(int64_t)p * G + e] = o[e];
+        }
       }
     } else {
       // granules in, in pool order; whole rows out
@@ -201,101 +246,16 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
 #pragma unroll
       for (int j = 0; j < NIT; ++j) {
         const int gi = j * 64 + lane, t = gi / dch, c = gi % dch;
-        const int64_t off = (row0 + t) * H * D + (int64_t)h * D + c * G;
-        *reinterpret_cast<u32x4*>(k_out + off) = kg[j];
-        *reinterpret_cast<u32x4*>(v_out + off) = *reinterpret_cast<const u32x4*>(lt + t * PITCH + c * G);
+        if (in_run(t)) {
+          const int64_t off = (row0 + t) * H * D + (int64_t)h * D + c * G;
+          *reinterpret_cast<u32x4*>(k_out + off) = kg[j];
+          *reinterpret_cast<u32x4*>(v_out + off) = *reinterpret_cast<const u32x4*>(lt + t * PITCH + c * G);
+        }
       }
     }
-    return;
-  }
-
-  // ---------------- token groups of partly covered sub-blocks at the run's ends ----------------
-  // One thread moves a G x G micro-tile: G tokens of an aligned group x one granule of G dims.
-  const int64_t grp0 = ppos / G;
-  const int64_t grp1 = (ppos + npos - 1) / G;
-  const int64_t skip_lo = full_lo * (16 / G), skip_hi = full_hi * (16 / G);   // groups the bulk part moved
-  const int64_t n_groups = (grp1 - grp0 + 1) - (skip_hi - skip_lo);
-  const int64_t idx = (int64_t)(blockIdx.x - bulk_blocks) * blockDim.x + threadIdx.x;
-  const bool mine = run_ok && idx < n_groups * HC;
-  int64_t grp = grp0 + (mine ? idx / HC : 0);
-  if (grp >= skip_lo) grp += skip_hi - skip_lo;
-  const int hc = mine ? (int)(idx % HC) : 0;
-  const int h = hc / dch, c = hc % dch;
-  const int64_t tbase = grp * G;                       // first token of the aligned group
-  int lo = (int)((ppos > tbase ? ppos : tbase) - tbase);                          // valid tokens of
-  int hi = (int)(((ppos + npos) < (tbase + G) ? (ppos + npos) : (tbase + G)) - tbase);   // the group: [lo, hi)
-  if (!mine) lo = hi = 0;
-  const int64_t row0 = tbase - ppos;                   // contiguous-side row of group token 0
-  const int64_t col = (int64_t)h * D + c * G;
-
-  // contiguous-side loads first (unpack / append): they need nothing from the page table
-  Granule<T> krow[G], vrow[G];
-  if (MODE != MODE_PACK) {
-#pragma unroll
-    for (int i = 0; i < G; ++i) {
-      if (i >= lo && i < hi) {
-        const int64_t off = (row0 + i) * H * D + col;
-        krow[i].v = *reinterpret_cast<const uint4*>(k_plane + off);
-        vrow[i].v = *reinterpret_cast<const uint4*>(v_plane + off);
-      } else {
-        krow[i].v = make_uint4(0, 0, 0, 0);
-        vrow[i].v = make_uint4(0, 0, 0, 0);
-      }
-    }
-  }
-
-  // One aligned group never straddles a 16-token sub-block, hence never a page.
-  const int64_t lp = tbase / S;
-  const bool page_ok = mine && lp < npg;
-  const int page = page_ok ? b.page_indices[pbeg + lp] : -1;
-  if ((unsigned)page >= (unsigned)g.num_pages) return;
-  const int slot = (int)(tbase % S);
-  const int sub = slot >> 4, t16 = slot & 15;
-  char* head = g.layer_base + (int64_t)page * g.page_bytes;
-  T* kblk = reinterpret_cast<T*>(head + head_block_offset(0, h, S, D, sizeof(T))) + (int64_t)sub * 16 * D;
-  T* vblk = reinterpret_cast<T*>(head + head_block_offset(1, h, S, D, sizeof(T))) + (int64_t)sub * 16 * D;
-
-  if (MODE != MODE_PACK) {
-#pragma unroll
-    for (int i = 0; i < G; ++i)
-      if (i >= lo && i < hi)
-        *reinterpret_cast<uint4*>(kblk + k_sub_index(t16 + i, c * G, D, G)) = krow[i].v;
-    if (lo == 0 && hi == G) {
-#pragma unroll
-      for (int dd = 0; dd < G; ++dd) {
-        Granule<T> o;
-#pragma unroll
-        for (int i = 0; i < G; ++i) o.e[i] = vrow[i].e[dd];
-        *reinterpret_cast<uint4*>(vblk + v_sub_index(t16, c * G + dd)) = o.v;
-      }
-    } else {
-#pragma unroll
-      for (int dd = 0; dd < G; ++dd) {
-#pragma unroll
-        for (int i = 0; i < G; ++i)
-          if (i >= lo && i < hi) vblk[v_sub_index(t16 + i, c * G + dd)] = vrow[i].e[dd];
-      }
-    }
-  } else {
-    Granule<T> vcol[G];
-#pragma unroll
-    for (int dd = 0; dd < G; ++dd)
-      vcol[dd].v = *reinterpret_cast<const uint4*>(vblk + v_sub_index(t16, c * G + dd));
-#pragma unroll
-    for (int i = 0; i < G; ++i)
-      krow[i].v = *reinterpret_cast<const uint4*>(kblk + k_sub_index(t16 + i, c * G, D, G));
-#pragma unroll
-    for (int i = 0; i < G; ++i) {
-      if (i >= lo && i < hi) {
-        const int64_t off = (row0 + i) * H * D + col;
-        *reinterpret_cast<uint4*>(k_out + off) = krow[i].v;
-        Granule<T> o;
-#pragma unroll
-        for (int dd = 0; dd < G; ++dd) o.e[dd] = vcol[dd].e[i];
-        *reinterpret_cast<uint4*>(v_out + off) = o.v;
-      }
-    }
-  }
+  };
+  if (masked) move_sub_block(std::true_type{});
+  else move_sub_block(std::false_type{});
 }
 
 template <typename T, int MODE, int DCH>
@@ -315,16 +275,15 @@ hipError_t launch_move(const PoolGeom& g, const SegDev& segs, const BatchDev& b,
   if (runs <= 0 || max_run_tokens <= 0 || layers <= 0) return hipSuccess;
   if (layers > 65535) return hipErrorInvalidValue;
   const int G = 16 / g.es;
-  // Runs of at least 128 tokens: whole sub-blocks of the longest run x heads, one per wavefront,
-  // then the groups of at most two partly covered sub-blocks per run (2 * 16/G groups, + 2).
-  // Shorter runs (a step's few new tokens) are latency-bound, and one thread per group with
-  // fewer, smaller workgroups finishes sooner: all their groups take the group path.
+  // One wavefront per (16-token sub-block, head).  Runs of at least 128 tokens: the sub-blocks a
+  // run covers completely (of the longest run) take the unmasked form, the at most two partly
+  // covered ones at its ends the masked form.  Shorter runs (a step's few new tokens): every
+  // sub-block a run touches, at most ceil(max / 16) + 1, takes the masked form.
   const bool bulk = max_run_tokens >= 128;
   const int64_t bulk_units = bulk ? (max_run_tokens / 16) * (int64_t)g.H : 0;
   const int64_t bulk_blocks = (bulk_units + kBulkWaves - 1) / kBulkWaves;
-  const int64_t edge_groups = bulk ? (2 * (16 / G) + 2) : (max_run_tokens / G + 2);
-  const int64_t edge_work = edge_groups * (int64_t)g.H * (g.D / G);
-  const int64_t blocks = bulk_blocks + (edge_work + 255) / 256;
+  const int64_t end_units = (bulk ? 2 : (max_run_tokens + 15) / 16 + 1) * (int64_t)g.H;
+  const int64_t blocks = bulk_blocks + (end_units + kBulkWaves - 1) / kBulkWaves;
   if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
   dim3 grid((unsigned)blocks, (unsigned)runs, (unsigned)layers);
   const int dch = g.D / G;
