@@ -5,13 +5,13 @@
 
 A step is one pass of the whole hot path over one batch of the synthetic workload: the batch's
 cache-miss users are restored from an HBM-resident staging buffer (mts_kv_unpack_layers), every
-layer runs its attention over the cached prefix plus the step's own K/V rows
-(mts_attn_incremental_unappended), the rows of all layers are then written to the pool
-(mts_kv_append_layers, Alg. 1 step 8.2 deferred to the end of the loop) and the users chosen for
-offload are gathered (mts_kv_pack_layers, Alg. 1 step 9).  --append-first and --restore-sync layer
-select Alg. 1's literal order and stream structure instead (append before each layer's attention;
-scatter on a side stream with one event per layer, step 8.3).  All inputs are resident in HBM
-before the timed region.
+layer appends the step's K/V rows (mts_kv_append, Alg. 1 step 8.2) and runs its attention over
+the cached prefix plus those rows (mts_attn_incremental, step 8.4), and the users chosen for
+offload are gathered after the layer loop (mts_kv_pack_layers, step 9); all on one stream.
+--restore-sync layer selects Alg. 1's stream structure instead (scatter on a side stream with one
+event per layer, step 8.3; gather on the side stream), --deferred-append the attention that
+reads the step's rows directly, with one append of all layers after the loop.  All inputs are
+resident in HBM before the timed region.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -47,10 +47,11 @@ def parse():
                          "\"serving_trace\" object to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
-    ap.add_argument("--append-first", action="store_true",
-                    help="diagnostic: Alg. 1's order layer by layer (mts_kv_append, then mts_attn_incremental "
-                         "reading the rows back from the pool) instead of the unappended attention with one "
-                         "append of all layers after the loop")
+    ap.add_argument("--deferred-append", action="store_true",
+                    help="the attention takes the step's K/V rows from k_new / v_new itself "
+                         "(mts_attn_incremental_unappended) and all layers' rows are appended by one launch after "
+                         "the layer loop, instead of Alg. 1's order (mts_kv_append, then mts_attn_incremental "
+                         "reading the rows back from the pool)")
     ap.add_argument("--restore-sync", choices=["step", "layer"], default="step",
                     help="restored users' staged histories (already in HBM here): 'step' scatters all layers with "
                          "one launch ahead of layer 0 and gathers the offload after the appends, all on one stream; "
@@ -426,12 +427,14 @@ def main():
     pointwise = args.attention == "pointwise"
     inv_norm = 1.0 / max(1, int(w.total_lens.max()))
 
-    # Default: the attention takes the step's rows from k_new / v_new itself and every layer's rows are
-    # written to the pool by ONE launch after the layer loop (a serving engine keeps the L small row
-    # buffers of a step alive until then), so no copy sits between two layers' attentions.  Long new
-    # segments (read from the pool by the dense-prefill kernel) keep Alg. 1's order: append, then attention.
-    deferred_append = not args.append_first and not mts.mts_attn_unappended_appends(cache.desc, batch.meta)
-    append_first = not deferred_append                    # such shapes take Alg. 1's order, call by call
+    # Default: Alg. 1's order, layer by layer - 8.2 append, then 8.4 attention reads the rows back from
+    # the pool.  --deferred-append: the attention takes the step's rows from k_new / v_new itself and
+    # every layer's rows are written to the pool by ONE launch after the layer loop (a serving engine
+    # keeps the L small row buffers of a step alive until then), so no copy sits between two layers'
+    # attentions.  Long new segments (read from the pool by the dense-prefill kernel) always keep
+    # Alg. 1's order.
+    deferred_append = args.deferred_append and not mts.mts_attn_unappended_appends(cache.desc, batch.meta)
+    append_first = not deferred_append
     rows_stride = k_new.stride(0) * k_new.element_size()
 
     # 'layer': the paper's stream structure - scatter on the side stream with one event per layer that
