@@ -142,7 +142,12 @@ AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   p.q_tile = roundup(max_new, 16) < 64 ? roundup(max_new, 16) : 64;
   p.q_tiles_max = (max_new + p.q_tile - 1) / p.q_tile;
   const int64_t items = (int64_t)b.batch * p.q_tiles_max;
-  const int64_t tiles_upper = items * ((b.max_total_len + 31) / 32) * g.H;   // kv tiles of the call
+  // Every (query tile, head) also counts an allowance for what it costs besides streaming its
+  // tiles; measured optimum 6-12 tiles on three workloads (a flat one), worth 7 % of the launch
+  // where a share holds several short pairs and 1-2 % where pairs are longer than shares.
+  p.pair_cost = 8;
+  if (const char* env = getenv("MTS_ATTN_PAIR_COST")) { const int v = atoi(env); if (v >= 0 && v <= 64) p.pair_cost = v; }
+  const int64_t tiles_upper = items * ((b.max_total_len + 31) / 32 + 1 + p.pair_cost) * g.H;   // schedule units of the call
   if (items > 16384 || b.batch > 4096 || tiles_upper >= (1ll << 31)) { p.too_large = true; return p; }
   p.n_items = (int)items;
   // a wavefront's share is never shorter than this: below it, start-up and the partial

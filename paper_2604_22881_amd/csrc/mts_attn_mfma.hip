@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
                                                           const uint16_t* __restrict__ k_new,
                                                           const uint16_t* __restrict__ v_new,
                                                           uint16_t* __restrict__ out, float c, float inv_norm,
-                                                          int q_tiles_max, int n_items, int min_tiles,
+                                                          int q_tiles_max, int n_items, int min_tiles, int pair_cost,
                                                           MergeDesc* __restrict__ ws_desc,
                                                           float* __restrict__ ws_o,
                                                           float* __restrict__ ws_ml) {
@@ -149,13 +149,21 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     return (s_P[u] + q1 + kTile - 1) / kTile;
   };
 
+  // What a (query tile, head) costs in the schedule: its kv tiles plus an allowance, in tiles,
+  // for what it costs besides streaming (Q and page-id loads, the first tiles' latency, the
+  // masked tail, writing the result).  Shares are equal in this unit, so a share that holds
+  // several short pairs gets fewer tiles than one inside a long pair.
+  auto item_cost = [&](int item) -> int {
+    const int t = item_tiles(item);
+    return t > 0 ? t + pair_cost : 0;
+  };
   // ---- schedule: every workgroup computes the same prefix sum --------------------------
   {
     const int per_thread = (n_items + 255) / 256;
     const int first = tid * per_thread;
     int local = 0;
     for (int k = 0; k < per_thread; ++k)
-      if (first + k < n_items) local += item_tiles(first + k) * H;
+      if (first + k < n_items) local += item_cost(first + k) * H;
     int incl = local;                                  // inclusive scan over the wavefront
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -169,7 +177,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     for (int k = 0; k < per_thread; ++k) {
       if (first + k < n_items) {
         s_cum[first + k] = base;
-        base += item_tiles(first + k) * H;
+        base += item_cost(first + k) * H;
       }
     }
     if (tid == 255) s_cum[n_items] = base;
@@ -212,12 +220,20 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     const int pool_tiles = (P + kTile - 1) / kTile;    // unappended: tiles of the cached prefix
     // kv tiles of the whole (query tile, head)
     const int tiles = FRESH ? pool_tiles + (q1 + kTile - 1) / kTile : (P + q1 + kTile - 1) / kTile;
+    // Positions count cost units: a pair's allowance comes first, then its tiles.
     const int item_pos = uniform(s_cum[item]);
-    const int h = (pos - item_pos) / tiles;
-    const int t_beg = (pos - item_pos) % tiles;
-    const int pair_end = item_pos + (h + 1) * tiles;
+    const int ctiles = tiles + pair_cost;
+    const int h = (pos - item_pos) / ctiles;
+    const int c_beg = (pos - item_pos) % ctiles;
+    const int pair_end = item_pos + (h + 1) * ctiles;
     const int seg_end = pair_end < hi ? pair_end : hi;
-    const int t_end = t_beg + (seg_end - pos);
+    const int c_end = c_beg + (seg_end - pos);
+    const int t_beg = c_beg > pair_cost ? c_beg - pair_cost : 0;
+    const int t_end = c_end > pair_cost ? c_end - pair_cost : 0;
+    if (t_end <= t_beg) {                              // only the pair's allowance lies in this share
+      pos = seg_end;
+      continue;
+    }
     const int nqb = (nq + 15) >> 4;
     const int T_u = P + n_u;                           // tokens that hold data
     const int first_query_pos = P + q0;
@@ -717,7 +733,7 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
   float* ws_o = reinterpret_cast<float*>(ws + plan.ws_desc_bytes);
   float* ws_ml = ws_o + (int64_t)plan.max_waves * 2 * plan.q_tile * g.D;
   hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, k_new, v_new, out, c, inv_norm, plan.q_tiles_max,
-                     plan.n_items, plan.min_tiles, ws_desc, ws_o, ws_ml);
+                     plan.n_items, plan.min_tiles, plan.pair_cost, ws_desc, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_merge_kernel<D, PW>), dim3(wgs * kWavesPerWg, (plan.q_tile * (D / 4) + 255) / 256), dim3(256),

@@ -52,6 +52,7 @@ struct AttnPlan {
   int32_t q_tiles_max;   // ceil(max_new / q_tile)
   int32_t n_items;       // batch * q_tiles_max
   int32_t min_tiles;     // least kv tiles a wavefront's share may hold
+  int32_t pair_cost;     // schedule allowance per (query tile, head), in tiles
   int32_t max_waves;     // most wavefronts the launch may use (sizes the partial buffers)
   int64_t ws_desc_bytes; // per-wavefront merge descriptors at the start of the workspace
   int64_t ws_bytes;      // whole workspace
