@@ -155,14 +155,10 @@ AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   if (const char* env = getenv("MTS_ATTN_MIN_TILES")) { const int v = atoi(env); if (v >= 1) p.min_tiles = v; }
   int64_t waves = (tiles_upper + p.min_tiles - 1) / p.min_tiles;
   waves = (waves + 3) / 4 * 4;
-  // 256 CUs x 4 SIMDs, and a second wavefront per SIMD once every share is long enough to
-  // repay the extra cuts (each cut costs a segment start-up and a pair of partial accumulators)
-  int64_t est_tiles = tiles_upper;
-  if (b.total_pages > 0) {
-    const int64_t paged = ((int64_t)b.total_pages * g.S + 31) / 32 * g.H * p.q_tiles_max;
-    if (paged < est_tiles) est_tiles = paged;
-  }
-  int64_t cap = est_tiles >= 2048 * 32 ? 2048 : 1024;
+  // 256 CUs x 4 SIMDs: one wavefront per SIMD.  A second one (the kernel is compiled to fit two)
+  // measured 2-5 % slower on every shape tried, small or large: it doubles the cuts, and the
+  // wavefront that starts second on a SIMD streams more slowly than the first.
+  int64_t cap = 1024;
   if (const char* env = getenv("MTS_ATTN_MAX_WAVES")) { const int v = atoi(env); if (v >= 4) cap = v / 4 * 4; }
   p.max_waves = (int)(waves < cap ? waves : cap);
   if (p.max_waves < 4) p.max_waves = 4;

@@ -3,7 +3,7 @@
 //
 // Schedule.  The work of one call is a single sequence of 32-token kv tiles, ordered by
 // (user, query tile, head, tile).  The launch is persistent: a fixed number of wavefronts
-// (one or two per SIMD) each take an equal, contiguous share of that sequence, so lognormal
+// (one per SIMD) each take an equal, contiguous share of that sequence, so lognormal
 // history lengths cost no imbalance and every K/V byte is read from HBM exactly once.  Every
 // workgroup derives the schedule by itself from the device-resident lengths (a prefix sum in
 // LDS), so the host needs no copy of them.  A wavefront that covers a whole (query tile,
@@ -741,10 +741,10 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
   return hipGetLastError();
 }
 
-// Launch shapes.  D <= 64: two wavefronts per SIMD with two tiles each in flight - the second
-// wavefront covers the first one's segment start-up and overlaps its VALU work with MFMA work.
-// D = 128: the accumulators and a useful ring need more than half the register file, so one
-// wavefront per SIMD with a deeper ring (3 tiles up to 32 queries per tile, else 2).
+// Launch shapes.  One wavefront per SIMD in every shape (the planner caps the launch at 1024
+// wavefronts).  D <= 64: two tiles in flight, compiled to at most 256 registers - the same code
+// compiled for 512 registers, or with a ring of 3 or 4 tiles, measured 0-3 % slower.  D = 128:
+// a ring of 3 tiles up to 32 queries per tile, else 2.
 template <int D, bool PW, bool FRESH>
 hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, const uint16_t* k_new,
                     const uint16_t* v_new, uint16_t* out, const BatchDev& b, float c, float inv_norm, void* ws,
