@@ -39,9 +39,10 @@
 // Unappended mode (template flag FRESH).  The step's own K/V rows are taken from k_new / v_new
 // ([token][H][D], the layout the projection writes) instead of the pool, so the call does not
 // depend on the layer's append (Sec. 2: the context is the cached prefix followed by the new
-// rows) and the append can run beside it on another stream.  Only the few tiles at the end of
-// a (query tile, head) that hold new tokens take this path: a K fragment is still one 16-byte
-// load per lane (from the token's row), a V^T fragment is gathered element by element.
+// rows) and the append can happen later, for all layers at once.  A (query tile, head) is then
+// the tiles of the prefix followed by tiles of new rows, tiled from the first new token; for
+// the latter a K fragment is still one 16-byte load per lane (from the token's row), a V^T
+// fragment is gathered element by element.
 #include <math.h>
 
 #include <type_traits>
