@@ -243,6 +243,32 @@ int32_t mts_attn_pointwise_unappended(const mts_cache_desc* cache, int32_t layer
                                       const mts_batch_meta* meta, float sm_scale, float inv_norm,
                                       void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * mts_attn_incremental_unappended for a batch in which some users' cached prefix has not been
+ * scattered yet and still lies in the contiguous onload buffer (Sec. 4.1: the buffer doubles as
+ * an inference area, so that a restored user's attention need not wait for the scatter kernel).
+ *   staged_rows       device, the layer's runs one after another, each [2][n][H][D] as for
+ *                     mts_kv_unpack, 16-byte aligned
+ *   staged_first_run  device [batch]: index of the first run of user u's prefix, or -1 if the
+ *                     prefix is in the pool; a staged user's prefix is covered by consecutive runs
+ *                     of exactly chunk_tokens tokens each, the last one holding the rest
+ *   staged_run_tok    device [runs + 1]: token offset of every run in staged_rows (run s starts
+ *                     at element staged_run_tok[s] * 2 * H * D), as seg_tok_indptr of mts_kv_unpack
+ *   chunk_tokens      tokens per run, a positive multiple of 32
+ * The pool's pages of a staged user are neither read nor written (they must still be allotted
+ * in the page table: mts_kv_unpack and the append fill them afterwards).  Served by the
+ * streaming bf16 kernel only; MTS_ERR_UNSUPPORTED for fp32 caches and for the long new segments
+ * the dense-prefill kernel serves (there, unpack first).  Rows of the onload buffer are read
+ * element-wise for V (a transpose by addressing), several times slower per token than pool
+ * tiles: meant for the few restored users of a batch.
+ */
+int32_t mts_attn_incremental_staged(const mts_cache_desc* cache, int32_t layer, const void* q,
+                                    const void* k_new, const void* v_new, const void* staged_rows,
+                                    const int32_t* staged_first_run, const int64_t* staged_run_tok,
+                                    int32_t chunk_tokens, void* out, const mts_batch_meta* meta,
+                                    float sm_scale, void* workspace, int64_t workspace_bytes,
+                                    void* stream);
+
 /* Host<->device staging copies on `stream` (hipMemcpyAsync); `host` should be pinned for the
  * copy to be asynchronous (Sec. 4.2, DMA between pinned buffers and the onload / offload buffers). */
 int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream);

@@ -23,6 +23,7 @@ EXPORTS = (
     "mts_kv_unpack_layers", "mts_kv_pack_layers", "mts_kv_append_layers",
     "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_pointwise",
     "mts_attn_unappended_appends", "mts_attn_incremental_unappended", "mts_attn_pointwise_unappended",
+    "mts_attn_incremental_staged",
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
     "mts_xfer_create", "mts_xfer_destroy", "mts_xfer_onload_submit", "mts_xfer_onload_wait_layer",
     "mts_xfer_offload_submit", "mts_xfer_offload_pending_tokens", "mts_xfer_drain",
@@ -96,6 +97,7 @@ def lib():
         "mts_attn_unappended_appends": (I32, [DESC, META]),
         "mts_attn_incremental_unappended": (I32, [DESC, I32, P, P, P, P, META, F32, P, I64, P]),
         "mts_attn_pointwise_unappended": (I32, [DESC, I32, P, P, P, P, META, F32, F32, P, I64, P]),
+        "mts_attn_incremental_staged": (I32, [DESC, I32, P, P, P, P, P, P, I32, P, META, F32, P, I64, P]),
         "mts_stage_h2d_async": (I32, [P, P, I64, P]),
         "mts_stage_d2h_async": (I32, [P, P, I64, P]),
         "mts_xfer_create": (I32, [C.POINTER(XferConfig), C.POINTER(P)]),
@@ -248,6 +250,14 @@ def mts_attn_pointwise_unappended(desc, layer, q, k_new, v_new, out, meta, inv_n
     return _check(lib().mts_attn_pointwise_unappended(C.byref(desc), layer, _ptr(q), _ptr(k_new), _ptr(v_new),
                                                       _ptr(out), C.byref(meta), float(sm_scale), float(inv_norm),
                                                       _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def mts_attn_incremental_staged(desc, layer, q, k_new, v_new, staged_rows, staged_first_run, staged_run_tok,
+                                chunk_tokens, out, meta, sm_scale=0.0, workspace=None, workspace_bytes=0, stream=None):
+    return _check(lib().mts_attn_incremental_staged(C.byref(desc), layer, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                    _ptr(staged_rows), _ptr(staged_first_run), _ptr(staged_run_tok),
+                                                    int(chunk_tokens), _ptr(out), C.byref(meta), float(sm_scale),
+                                                    _ptr(workspace), int(workspace_bytes), _stream(stream)))
 
 
 # ---- transfer pipeline --------------------------------------------------------------------

@@ -334,7 +334,8 @@ bool rows_fit_32bit(const mts::PoolGeom& g, const mts::BatchDev& b) {
 int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
                        const mts_batch_meta* meta, float sm_scale, float inv_norm, void* workspace,
                        int64_t workspace_bytes, void* stream, bool unappended = false,
-                       const void* k_new = nullptr, const void* v_new = nullptr) {
+                       const void* k_new = nullptr, const void* v_new = nullptr,
+                       const mts::StagedHistories* hist = nullptr) {
   mts::PoolGeom g{};
   mts::BatchDev b{};
   int32_t st;
@@ -366,7 +367,10 @@ int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t la
   const bool plain = getenv("MTS_ATTN_PLAIN") != nullptr;
   if (plan.use_mfma && !plan.use_prefill && !plain && !(unappended && !rows_fit_32bit(g, b)))
     return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, inv_norm, plan.ws_bytes > 0 ? workspace : nullptr, s,
-                                            unappended ? k_new : nullptr, unappended ? v_new : nullptr), name);
+                                            unappended ? k_new : nullptr, unappended ? v_new : nullptr, hist), name);
+  if (hist)
+    return fail(MTS_ERR_UNSUPPORTED, "histories in the onload buffer are read by the streaming bf16 kernel only "
+                "(short new segments): unpack them first for this shape");
   // The other kernels read every key from the pool: an unappended call writes the rows there
   // first, on the same stream (a long new segment or fp32 elements; the copy is a small part
   // of such a call).
@@ -424,6 +428,23 @@ int32_t mts_attn_pointwise_unappended(const mts_cache_desc* cache, int32_t layer
     return fail(MTS_ERR_INVALID_ARG, "inv_norm must be finite and > 0");
   return attention_call("mts_attn_pointwise_unappended launch", cache, layer, q, out, meta, sm_scale, inv_norm,
                         workspace, workspace_bytes, stream, true, k_new, v_new);
+}
+
+int32_t mts_attn_incremental_staged(const mts_cache_desc* cache, int32_t layer, const void* q, const void* k_new,
+                                    const void* v_new, const void* staged_rows, const int32_t* staged_first_run,
+                                    const int64_t* staged_run_tok, int32_t chunk_tokens, void* out,
+                                    const mts_batch_meta* meta, float sm_scale, void* workspace,
+                                    int64_t workspace_bytes, void* stream) {
+  if (!staged_rows || !staged_first_run || !staged_run_tok)
+    return fail(MTS_ERR_INVALID_ARG, "staged_rows / staged_first_run / staged_run_tok is NULL");
+  if (!aligned(staged_rows, 16)) return fail(MTS_ERR_INVALID_ARG, "staged_rows is not 16-byte aligned");
+  if (chunk_tokens <= 0 || chunk_tokens % 32 != 0)
+    return fail(MTS_ERR_INVALID_ARG, "chunk_tokens must be a positive multiple of 32");
+  if (cache && (int64_t)chunk_tokens * cache->num_heads * cache->head_dim * 4 >= (1ll << 31))
+    return fail(MTS_ERR_UNSUPPORTED, "a run of %d tokens exceeds 2 GiB", chunk_tokens);
+  const mts::StagedHistories hist{staged_rows, staged_first_run, staged_run_tok, chunk_tokens};
+  return attention_call("mts_attn_incremental_staged launch", cache, layer, q, out, meta, sm_scale, 0.f, workspace,
+                        workspace_bytes, stream, true, k_new, v_new, &hist);
 }
 
 int32_t mts_stage_h2d_async(void* device_dst, const void* host_src, int64_t bytes, void* stream) {

@@ -90,6 +90,17 @@ __device__ __forceinline__ void wave_share(int total, int num_waves, int min_til
   *hi = (l + per) < total ? (int)(l + per) : total;
 }
 
+// Histories that are still in the contiguous onload buffer (Sec. 4.1: the buffer doubles as an
+// inference area).  User u's prefix is runs first_run[u], first_run[u] + 1, ... of `chunk` tokens
+// each (the last one shorter), run s holding [2][n_s][H][D] at element run_tok[s] * 2 * H * D of
+// `rows`; first_run[u] < 0: the user's prefix is in the pool.  first_run == nullptr: nobody's is.
+struct StagedRuns {
+  const uint16_t* rows;
+  const int32_t*  first_run;
+  const int64_t*  run_tok;
+  int32_t         chunk;       // tokens per run, a multiple of 32
+};
+
 // What the merge kernel needs to finish one (query tile, head) cut by share boundaries;
 // written by the wavefront that holds the pair's first tile.
 struct MergeDesc {
@@ -107,6 +118,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
                                                           const uint16_t* __restrict__ q,
                                                           const uint16_t* __restrict__ k_new,
                                                           const uint16_t* __restrict__ v_new,
+                                                          StagedRuns staged,
                                                           uint16_t* __restrict__ out, float c, float inv_norm,
                                                           int q_tiles_max, int n_items, int min_tiles, int pair_cost,
                                                           MergeDesc* __restrict__ ws_desc,
@@ -331,42 +343,62 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
     // loads of a tile are in flight together; the ring has drained by then, so its registers
     // are free.
     const int row_bytes = H * D * 2;
-    __amdgpu_buffer_rsrc_t k_rows, v_rows;
+    auto row_source = [&](const uint16_t* first_row, int rows) __attribute__((always_inline)) {
+      return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(first_row), 0, (rows - 1) * row_bytes + D * 2,
+                                               0x00020000);
+    };
+    __amdgpu_buffer_rsrc_t k_rows, v_rows;             // the user's new rows of this head
+    int first_run = -1;                                // >= 0: the prefix is read from the onload buffer
     if constexpr (FRESH) {
       const int64_t first = ((int64_t)tok0 * H + h) * D;
-      const int span = (n_u - 1) * row_bytes + D * 2;
-      k_rows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(k_new + first), 0, span, 0x00020000);
-      v_rows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(v_new + first), 0, span, 0x00020000);
+      k_rows = row_source(k_new + first, n_u);
+      v_rows = row_source(v_new + first, n_u);
+      if (staged.first_run != nullptr) first_run = uniform(staged.first_run[u]);
     }
     // the pool's slot order: token of the K row this lane holds in half-tile 0 (half-tile 1: + 4)
     const int k_lane_pos = ((r >> 3) << 4) + (((r & 7) >> 2) << 3) + (r & 3);
-    auto load_fresh_k = [&](auto buf, int ft) __attribute__((always_inline)) {
+    // Loads the 32 rows from `row_first` on of a row source as one tile into ring slot p.
+    auto load_rows_k = [&](auto buf, __amdgpu_buffer_rsrc_t ks, int row_first) __attribute__((always_inline)) {
       constexpr int p = decltype(buf)::value;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        int koff = (ft * kTile + k_lane_pos + 4 * hf) * row_bytes + 8 * gq * 2;
+        int koff = (row_first + k_lane_pos + 4 * hf) * row_bytes + 8 * gq * 2;
         asm volatile("" : "+v"(koff));                 // computed here, not kept in a register across the ring
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-          kf[p][hf][s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(k_rows, koff + 32 * s * 2, 0, 0));
+          kf[p][hf][s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(ks, koff + 32 * s * 2, 0, 0));
       }
     };
-    auto load_fresh = [&](auto buf, int ft) __attribute__((always_inline)) {
+    auto load_rows = [&](auto buf, __amdgpu_buffer_rsrc_t ks, __amdgpu_buffer_rsrc_t vs, int row_first)
+        __attribute__((always_inline)) {
       constexpr int p = decltype(buf)::value;
-      load_fresh_k(buf, ft);
-      int voff = (ft * kTile + 8 * gq) * row_bytes + r * 2;           // first of this lane's 8 tokens
+      load_rows_k(buf, ks, row_first);
+      int voff = (row_first + 8 * gq) * row_bytes + r * 2;            // first of this lane's 8 tokens
       asm volatile("" : "+v"(voff));                   // the 8 row offsets are formed per load, not hoisted
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         uint32_t f[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          f[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(v_rows, voff + e * row_bytes + 32 * db, 0, 0);
+          f[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(vs, voff + e * row_bytes + 32 * db, 0, 0);
         u32x4 v;
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = f[2 * j] | (f[2 * j + 1] << 16);
         vf[p][db] = __builtin_bit_cast(bf16x8, v);
       }
+    };
+    // Tile `tile` of a prefix that lies in the onload buffer: the run that holds it (tiles never
+    // straddle runs: the run length is a multiple of 32) is its own row source, K plane then V
+    // plane, so rows past the run's (and with the last run, the prefix's) end read as 0.
+    auto staged_sources = [&](int tile, __amdgpu_buffer_rsrc_t& ks, __amdgpu_buffer_rsrc_t& vs, int& row_first)
+        __attribute__((always_inline)) {
+      const int run = (tile * kTile) / staged.chunk;
+      const int64_t a = staged.run_tok[first_run + run], e = staged.run_tok[first_run + run + 1];
+      const int rows = (int)(e - a);
+      const uint16_t* kp = staged.rows + a * 2 * H * D + (int64_t)h * D;
+      ks = row_source(kp, rows);
+      vs = row_source(kp + (int64_t)rows * H * D, rows);
+      row_first = tile * kTile - run * staged.chunk;
     };
 
     // S^T of query block qb against the K fragments of ring slot p.  The lane holds, for query
@@ -448,17 +480,26 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
       for (int qb = 0; qb < NQ; ++qb) mx[qb] = -INFINITY;
       if constexpr (FRESH) { mask_q0 = P - 1; mask_qstep = 0; }
       for (int tile = t_beg; tile < ring_end; ++tile) {
-        int id0, id1;
-        page_ids_at(tile, id0, id1);
-        const char *kb0, *kb1;
-        tile_bases_at(tile, id0, id1, kb0, kb1);
-        const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
         const int tb = tile * kTile;
+        if (FRESH && first_run >= 0) {
+          if constexpr (FRESH) {
+            __amdgpu_buffer_rsrc_t ks, vs;
+            int row_first;
+            staged_sources(tile, ks, vs, row_first);
+            load_rows_k(std::integral_constant<int, 0>{}, ks, row_first);
+          }
+        } else {
+          int id0, id1;
+          page_ids_at(tile, id0, id1);
+          const char *kb0, *kb1;
+          tile_bases_at(tile, id0, id1, kb0, kb1);
+          const char* kl = ((r < 8) ? kb0 : kb1) + (r & 7) * 16;
 #pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
+          for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-          for (int s = 0; s < KS; ++s)
-            kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16);
+            for (int s = 0; s < KS; ++s)
+              kf[0][hf][s] = *reinterpret_cast<const bf16x8*>(kl + ((hf * (D / 8) + 4 * s + gq) * 8) * 16);
+        }
 #pragma unroll
         for (int qb = 0; qb < NQ; ++qb) {
           f32x4 s0, s1;
@@ -470,7 +511,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         mask_q0 = first_query_pos; mask_qstep = 1;
         for (int tile = fresh_beg; tile < t_end; ++tile) {
           const int tb = P + (tile - pool_tiles) * kTile;
-          load_fresh_k(std::integral_constant<int, 0>{}, tile - pool_tiles);
+          load_rows_k(std::integral_constant<int, 0>{}, k_rows, (tile - pool_tiles) * kTile);
 #pragma unroll
           for (int qb = 0; qb < NQ; ++qb) {
             f32x4 s0, s1;
@@ -518,7 +559,19 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         }
 
         if constexpr (FRESH) { mask_q0 = P - 1; mask_qstep = 0; valid_end = P; }
-        if (!FRESH || ring_end > t_beg) {
+        if (FRESH && first_run >= 0) {
+          // the prefix lies in the onload buffer: its tiles come through the row loader, one at a time
+          if constexpr (FRESH) {
+            for (int tile = t_beg; tile < ring_end; ++tile) {
+              __amdgpu_buffer_rsrc_t ks, vs;
+              int row_first;
+              staged_sources(tile, ks, vs, row_first);
+              load_rows(std::integral_constant<int, 0>{}, ks, vs, row_first);
+              if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0(tile * kTile);
+              tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile * kTile);
+            }
+          }
+        } else if (!FRESH || ring_end > t_beg) {
           page_ids(t_beg, idr0[0], idr1[0]);
           if constexpr (PF > 1) page_ids(t_beg + 1, idr0[1], idr1[1]);
           if constexpr (PF > 2) page_ids(t_beg + 2, idr0[2], idr1[2]);
@@ -569,7 +622,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
           mask_q0 = first_query_pos; mask_qstep = 1; valid_end = T_u;
           for (int tile = fresh_beg; tile < t_end; ++tile) {      // the tiles of new rows
             const int ft = tile - pool_tiles;
-            load_fresh(std::integral_constant<int, 0>{}, ft);
+            load_rows(std::integral_constant<int, 0>{}, k_rows, v_rows, ft * kTile);
             if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0(P + ft * kTile);
             tile_step(nq_c, tail, std::integral_constant<int, 0>{}, P + ft * kTile);
           }
@@ -705,8 +758,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ 
 
 template <int D, int NQB, int PF, int WPS, bool PW, bool FRESH>
 hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, const uint16_t* k_new,
-                      const uint16_t* v_new, uint16_t* out, const BatchDev& b, float c, float inv_norm,
-                      void* workspace, hipStream_t stream) {
+                      const uint16_t* v_new, const StagedRuns& staged, uint16_t* out, const BatchDev& b, float c,
+                      float inv_norm, void* workspace, hipStream_t stream) {
   auto kern = attn_stream_kernel<D, NQB, PF, WPS, PW, FRESH>;
   const size_t lds_bytes = sizeof(int) * ((size_t)3 * b.batch + 2 + plan.n_items + 1 + kWavesPerWg);
   static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
@@ -733,7 +786,7 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
   MergeDesc* ws_desc = reinterpret_cast<MergeDesc*>(ws);
   float* ws_o = reinterpret_cast<float*>(ws + plan.ws_desc_bytes);
   float* ws_ml = ws_o + (int64_t)plan.max_waves * 2 * plan.q_tile * g.D;
-  hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, k_new, v_new, out, c, inv_norm, plan.q_tiles_max,
+  hipLaunchKernelGGL(kern, dim3(wgs), dim3(256), lds_bytes, stream, g, b, q, k_new, v_new, staged, out, c, inv_norm, plan.q_tiles_max,
                      plan.n_items, plan.min_tiles, plan.pair_cost, ws_desc, ws_o, ws_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -748,8 +801,8 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
 // a ring of 3 tiles up to 32 queries per tile, else 2.
 template <int D, bool PW, bool FRESH>
 hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, const uint16_t* k_new,
-                    const uint16_t* v_new, uint16_t* out, const BatchDev& b, float c, float inv_norm, void* ws,
-                    hipStream_t stream) {
+                    const uint16_t* v_new, const StagedRuns& staged, uint16_t* out, const BatchDev& b, float c,
+                    float inv_norm, void* ws, hipStream_t stream) {
 #ifndef MTS_PF_A
 #define MTS_PF_A 2   // D <= 64
 #define MTS_PF_B 3   // D = 128, up to 32 queries per tile
@@ -758,12 +811,14 @@ hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, 
 #endif
   constexpr int PF_SMALL = (D == 128) ? MTS_PF_B : MTS_PF_A;
   constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;
-  constexpr int WPS = (D == 128) ? 1 : MTS_WPS_A;
+  // the unappended kernels carry the row loader as well: compiled for one wavefront per SIMD
+  // (which is what runs), they need no spills
+  constexpr int WPS = (D == 128 || FRESH) ? 1 : MTS_WPS_A;
   switch (plan.q_tile / 16) {
-    case 1: return launch_one<D, 1, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
-    case 2: return launch_one<D, 2, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
-    case 3: return launch_one<D, 3, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
-    default: return launch_one<D, 4, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, out, b, c, inv_norm, ws, stream);
+    case 1: return launch_one<D, 1, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
+    case 2: return launch_one<D, 2, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
+    case 3: return launch_one<D, 3, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
+    default: return launch_one<D, 4, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
   }
 }
 
@@ -771,7 +826,7 @@ hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, 
 
 hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
                             const BatchDev& b, float sm_scale, float inv_norm, void* workspace,
-                            hipStream_t stream, const void* k_new, const void* v_new) {
+                            hipStream_t stream, const void* k_new, const void* v_new, const StagedHistories* hist) {
   if (b.total_new <= 0 || b.batch <= 0) return hipSuccess;
   const bool pw = inv_norm > 0.f;
   // pointwise: the scale stays in natural units; softmax: logits are exponentiated in base 2
@@ -781,12 +836,15 @@ hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void*
   const uint16_t* vp = reinterpret_cast<const uint16_t*>(v_new);
   uint16_t* op = reinterpret_cast<uint16_t*>(out);
   const bool fresh = kp != nullptr;
+  StagedRuns staged{nullptr, nullptr, nullptr, 32};
+  if (fresh && hist != nullptr)
+    staged = StagedRuns{reinterpret_cast<const uint16_t*>(hist->rows), hist->first_run, hist->run_tok, hist->chunk};
 #define MTS_ATTN_CASE(D_)                                                                                        \
   case D_:                                                                                                       \
-    if (pw) return fresh ? launch_d<D_, true, true>(g, plan, qp, kp, vp, op, b, c, inv_norm, workspace, stream)   \
-                         : launch_d<D_, true, false>(g, plan, qp, kp, vp, op, b, c, inv_norm, workspace, stream); \
-    return fresh ? launch_d<D_, false, true>(g, plan, qp, kp, vp, op, b, c, 0.f, workspace, stream)               \
-                 : launch_d<D_, false, false>(g, plan, qp, kp, vp, op, b, c, 0.f, workspace, stream);
+    if (pw) return fresh ? launch_d<D_, true, true>(g, plan, qp, kp, vp, staged, op, b, c, inv_norm, workspace, stream)   \
+                         : launch_d<D_, true, false>(g, plan, qp, kp, vp, staged, op, b, c, inv_norm, workspace, stream); \
+    return fresh ? launch_d<D_, false, true>(g, plan, qp, kp, vp, staged, op, b, c, 0.f, workspace, stream)               \
+                 : launch_d<D_, false, false>(g, plan, qp, kp, vp, staged, op, b, c, 0.f, workspace, stream);
   switch (g.D) {
     MTS_ATTN_CASE(32)
     MTS_ATTN_CASE(64)

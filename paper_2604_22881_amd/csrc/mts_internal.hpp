@@ -66,10 +66,20 @@ hipError_t launch_attn_generic(const PoolGeom& g, const void* q, void* out, cons
 bool attn_prefill_applicable(const PoolGeom& g, const BatchDev& b);
 hipError_t launch_attn_prefill(const PoolGeom& g, const void* q, void* out, const BatchDev& b,
                                float sm_scale, float inv_norm, hipStream_t stream);
+// Prefixes still in the contiguous onload buffer (device arrays; see mts_attn_incremental_staged).
+struct StagedHistories {
+  const void*    rows;        // the layer's runs, [2][n][H][D] each
+  const int32_t* first_run;   // [batch]: first run of user u's prefix, -1 = prefix in the pool
+  const int64_t* run_tok;     // [runs + 1]: token offset of every run in `rows`
+  int32_t        chunk;       // tokens per run (the last run of a user may be shorter)
+};
+
 // k_new / v_new non-NULL: this step's K/V rows ([token][H][D]) are read from there and the
-// pool's slots for them are not touched, so the layer's append need not have happened.
+// pool's slots for them are not touched, so the layer's append need not have happened; with
+// `hist`, the prefixes of the users it names are read from the onload buffer as well.
 hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void* q, void* out,
                             const BatchDev& b, float sm_scale, float inv_norm, void* workspace,
-                            hipStream_t stream, const void* k_new = nullptr, const void* v_new = nullptr);
+                            hipStream_t stream, const void* k_new = nullptr, const void* v_new = nullptr,
+                            const StagedHistories* hist = nullptr);
 
 }  // namespace mts

@@ -195,6 +195,23 @@ def test_unappended_attention_arguments():
     assert mts.mts_attn_unappended_appends(d, long_new) is True
 
 
+def test_staged_attention_arguments():
+    d, m = _desc(), _meta()
+    fn = mts.mts_attn_incremental_staged
+    ok = (d, 0, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, FAKE, m)
+    assert _code(fn, d, 0, FAKE, FAKE, FAKE, None, FAKE, FAKE, 64, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, FAKE, FAKE, FAKE, FAKE, None, FAKE, 64, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, FAKE, FAKE, FAKE, FAKE, FAKE, None, 64, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, FAKE, FAKE, FAKE, FAKE + 2, FAKE, FAKE, 64, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    for chunk in (0, 48, -64):
+        assert _code(fn, d, 0, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, chunk, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    assert _code(fn, d, 0, FAKE, None, FAKE, FAKE, FAKE, FAKE, 64, FAKE, m, stream=0) == B.MTS_ERR_INVALID_ARG
+    # shapes the streaming bf16 kernel does not serve
+    assert _code(fn, _desc(dtype=B.MTS_F32), *ok[1:], workspace=FAKE, workspace_bytes=1 << 30, stream=0) == B.MTS_ERR_UNSUPPORTED
+    long_new = _meta(batch=2, total_new=1024, max_new=512, max_total_len=600, total_pages=8)
+    assert _code(fn, *ok[:-1], long_new, stream=0) == B.MTS_ERR_UNSUPPORTED
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
