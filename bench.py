@@ -52,6 +52,10 @@ def parse():
                          "(mts_attn_incremental_unappended) and all layers' rows are appended by one launch after "
                          "the layer loop, instead of Alg. 1's order (mts_kv_append, then mts_attn_incremental "
                          "reading the rows back from the pool)")
+    ap.add_argument("--attend-staged", action="store_true",
+                    help="restored users' attention reads their histories straight from the staging (onload) "
+                         "buffer (mts_attn_incremental_staged, Sec. 4.1) and the scatter moves behind the layer "
+                         "loop, next to the deferred append; implies --deferred-append")
     ap.add_argument("--restore-sync", choices=["step", "layer"], default="step",
                     help="restored users' staged histories (already in HBM here): 'step' scatters all layers with "
                          "one launch ahead of layer 0 and gathers the offload after the appends, all on one stream; "
@@ -433,7 +437,16 @@ def main():
     # keeps the L small row buffers of a step alive until then), so no copy sits between two layers'
     # attentions.  Long new segments (read from the pool by the dense-prefill kernel) always keep
     # Alg. 1's order.
-    deferred_append = args.deferred_append and not mts.mts_attn_unappended_appends(cache.desc, batch.meta)
+    deferred_append = ((args.deferred_append or args.attend_staged)
+                       and not mts.mts_attn_unappended_appends(cache.desc, batch.meta))
+    attend_staged = args.attend_staged and deferred_append and miss_segs.num_segs > 0 and not pointwise
+    if attend_staged:
+        # runs of one user are consecutive in the segment list: first run per user, -1 = history in the pool
+        first_run = np.full(w.batch, -1, np.int32)
+        seg_users = miss_segs.seg_user.cpu().numpy()
+        for sidx in range(miss_segs.num_segs - 1, -1, -1):
+            first_run[seg_users[sidx]] = sidx
+        first_run_dev = torch.from_numpy(first_run).to(dev)
     append_first = not deferred_append
     rows_stride = k_new.stride(0) * k_new.element_size()
 
@@ -446,7 +459,9 @@ def main():
     xs = ss if per_layer else cs                          # stream of the scatter and the gather
 
     def step(attn_events=None):
-        if miss_segs.num_segs and per_layer:
+        if attend_staged:
+            pass                                            # scattered after the layer loop
+        elif miss_segs.num_segs and per_layer:
             for l in range(L):
                 mts.mts_kv_unpack(cache.desc, l, staging[l], *miss_segs.args(), batch.meta, stream=ss)
                 ev_unpacked[l].record(side)
@@ -456,7 +471,7 @@ def main():
             if append_first:
                 # Alg. 1's order: 8.2 append, then 8.4 attention reads the rows back from the pool
                 mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs)
-            if miss_segs.num_segs and per_layer:
+            if miss_segs.num_segs and per_layer and not attend_staged:
                 compute.wait_event(ev_unpacked[l])
             if attn_events is not None:
                 a, b = attn_events[l]
@@ -466,6 +481,10 @@ def main():
                     mts.mts_attn_pointwise(cache.desc, l, q[l], out[l], batch.meta, inv_norm, 0.0, ws, ws_bytes, stream=cs)
                 else:
                     mts.mts_attn_incremental(cache.desc, l, q[l], out[l], batch.meta, 0.0, ws, ws_bytes, stream=cs)
+            elif attend_staged:
+                mts.mts_attn_incremental_staged(cache.desc, l, q[l], k_new[l], v_new[l], staging[l], first_run_dev,
+                                                miss_segs.seg_tok_indptr, w.chunk_tokens, out[l], batch.meta, 0.0,
+                                                ws, ws_bytes, stream=cs)
             elif pointwise:
                 mts.mts_attn_pointwise_unappended(cache.desc, l, q[l], k_new[l], v_new[l], out[l], batch.meta, inv_norm,
                                                   0.0, ws, ws_bytes, stream=cs)
@@ -478,6 +497,8 @@ def main():
                 ev_appended[l].record(compute)
                 side.wait_event(ev_appended[l])
                 mts.mts_kv_pack(cache.desc, l, offload[l], *evict_segs.args(), batch.meta, stream=ss)
+        if attend_staged:
+            mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride, *miss_segs.args(), batch.meta, stream=cs)
         if deferred_append:
             mts.mts_kv_append_layers(cache.desc, 0, L, k_new, v_new, rows_stride, batch.meta, stream=cs)
         if evict_segs.num_segs and not (args.pack_per_layer and not deferred_append):
@@ -547,7 +568,7 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic", "launch": "eager" if args.eager else "hip_graph",
-        "restore_sync": args.restore_sync,
+        "restore_sync": args.restore_sync, "attend_staged": bool(attend_staged),
         "append": "all layers in one launch after the layer loop" if deferred_append else "per layer, before the attention",
         "config": {"workload": w.name, "seed": w.seed, "users": w.batch, "layers": L, "heads": H,
                    "head_dim": D, "page_size": w.page_size, "prefix_tokens": int(w.prefix_lens.sum()),

@@ -113,7 +113,9 @@ struct MergeDesc {
 };
 
 // WPS = wavefronts per SIMD the kernel is compiled for (bounds its registers)
-template <int D, int NQB, int PF, int WPS, bool PW, bool FRESH>
+// SRC = where keys and values come from: 0 the pool; 1 the step's own rows from k_new / v_new
+// (unappended); 2 also the prefixes of the users `staged` names, from the onload buffer
+template <int D, int NQB, int PF, int WPS, bool PW, int SRC>
 __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, BatchDev b,
                                                           const uint16_t* __restrict__ q,
                                                           const uint16_t* __restrict__ k_new,
@@ -124,6 +126,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
                                                           MergeDesc* __restrict__ ws_desc,
                                                           float* __restrict__ ws_o,
                                                           float* __restrict__ ws_ml) {
+  constexpr bool FRESH = SRC >= 1, STAGED = SRC == 2;
   constexpr int QT = 16 * NQB;       // queries per query tile
   constexpr int KS = D / 32;         // k-steps of Q.K
   constexpr int DB = D / 16;         // 16-dim blocks of the output
@@ -353,7 +356,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
       const int64_t first = ((int64_t)tok0 * H + h) * D;
       k_rows = row_source(k_new + first, n_u);
       v_rows = row_source(v_new + first, n_u);
-      if (staged.first_run != nullptr) first_run = uniform(staged.first_run[u]);
+      if constexpr (STAGED) first_run = uniform(staged.first_run[u]);
     }
     // the pool's slot order: token of the K row this lane holds in half-tile 0 (half-tile 1: + 4)
     const int k_lane_pos = ((r >> 3) << 4) + (((r & 7) >> 2) << 3) + (r & 3);
@@ -481,8 +484,8 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
       if constexpr (FRESH) { mask_q0 = P - 1; mask_qstep = 0; }
       for (int tile = t_beg; tile < ring_end; ++tile) {
         const int tb = tile * kTile;
-        if (FRESH && first_run >= 0) {
-          if constexpr (FRESH) {
+        if (STAGED && first_run >= 0) {
+          if constexpr (STAGED) {
             __amdgpu_buffer_rsrc_t ks, vs;
             int row_first;
             staged_sources(tile, ks, vs, row_first);
@@ -559,16 +562,27 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
         }
 
         if constexpr (FRESH) { mask_q0 = P - 1; mask_qstep = 0; valid_end = P; }
-        if (FRESH && first_run >= 0) {
-          // the prefix lies in the onload buffer: its tiles come through the row loader, one at a time
-          if constexpr (FRESH) {
-            for (int tile = t_beg; tile < ring_end; ++tile) {
+        if (STAGED && first_run >= 0) {
+          // the prefix lies in the onload buffer: its tiles come through the row loader, two ring
+          // slots in turn so that one tile's loads are in flight while the other is consumed (the
+          // loads are unconditional, clamped to the last tile, as in the ring)
+          if constexpr (STAGED) {
+            static_assert(PF >= 2, "two ring slots");
+            auto load_staged = [&](auto buf, int tile) __attribute__((always_inline)) {
               __amdgpu_buffer_rsrc_t ks, vs;
               int row_first;
-              staged_sources(tile, ks, vs, row_first);
-              load_rows(std::integral_constant<int, 0>{}, ks, vs, row_first);
-              if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0(tile * kTile);
-              tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile * kTile);
+              staged_sources(tile < ring_end - 1 ? tile : ring_end - 1, ks, vs, row_first);
+              load_rows(buf, ks, vs, row_first);
+            };
+            if (t_beg < ring_end) {
+              load_staged(std::integral_constant<int, 0>{}, t_beg);
+              for (int tile = t_beg; tile < ring_end; tile += 2) {
+                load_staged(std::integral_constant<int, 1>{}, tile + 1);
+                if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0(tile * kTile);
+                tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile * kTile);
+                load_staged(std::integral_constant<int, 0>{}, tile + 2);
+                if (tile + 1 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, (tile + 1) * kTile);
+              }
             }
           }
         } else if (!FRESH || ring_end > t_beg) {
@@ -756,11 +770,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(uint16_t* __restrict__ 
   *reinterpret_cast<bf16x4*>(out + ((int64_t)d.out_row + (int64_t)qi * H) * D + 4 * d4) = ob;
 }
 
-template <int D, int NQB, int PF, int WPS, bool PW, bool FRESH>
+template <int D, int NQB, int PF, int WPS, bool PW, int SRC>
 hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, const uint16_t* k_new,
                       const uint16_t* v_new, const StagedRuns& staged, uint16_t* out, const BatchDev& b, float c,
                       float inv_norm, void* workspace, hipStream_t stream) {
-  auto kern = attn_stream_kernel<D, NQB, PF, WPS, PW, FRESH>;
+  auto kern = attn_stream_kernel<D, NQB, PF, WPS, PW, SRC>;
   const size_t lds_bytes = sizeof(int) * ((size_t)3 * b.batch + 2 + plan.n_items + 1 + kWavesPerWg);
   static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
   static size_t lds_limit = 48 * 1024;
@@ -799,7 +813,7 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
 // wavefronts).  D <= 64: two tiles in flight, compiled to at most 256 registers - the same code
 // compiled for 512 registers, or with a ring of 3 or 4 tiles, measured 0-3 % slower.  D = 128:
 // a ring of 3 tiles up to 32 queries per tile, else 2.
-template <int D, bool PW, bool FRESH>
+template <int D, bool PW, int SRC>
 hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, const uint16_t* k_new,
                     const uint16_t* v_new, const StagedRuns& staged, uint16_t* out, const BatchDev& b, float c,
                     float inv_norm, void* ws, hipStream_t stream) {
@@ -811,14 +825,14 @@ hipError_t launch_d(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q, 
 #endif
   constexpr int PF_SMALL = (D == 128) ? MTS_PF_B : MTS_PF_A;
   constexpr int PF_LARGE = (D == 128) ? MTS_PF_C : MTS_PF_A;
-  // the unappended kernels carry the row loader as well: compiled for one wavefront per SIMD
-  // (which is what runs), they need no spills
-  constexpr int WPS = (D == 128 || FRESH) ? 1 : MTS_WPS_A;
+  // the kernels that also read the onload buffer keep two row tiles in flight beside everything
+  // else: compiled for one wavefront per SIMD (which is what runs), they need no spills
+  constexpr int WPS = (D == 128 || SRC == 2) ? 1 : MTS_WPS_A;
   switch (plan.q_tile / 16) {
-    case 1: return launch_one<D, 1, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
-    case 2: return launch_one<D, 2, PF_SMALL, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
-    case 3: return launch_one<D, 3, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
-    default: return launch_one<D, 4, PF_LARGE, WPS, PW, FRESH>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
+    case 1: return launch_one<D, 1, PF_SMALL, WPS, PW, SRC>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
+    case 2: return launch_one<D, 2, PF_SMALL, WPS, PW, SRC>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
+    case 3: return launch_one<D, 3, PF_LARGE, WPS, PW, SRC>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
+    default: return launch_one<D, 4, PF_LARGE, WPS, PW, SRC>(g, plan, q, k_new, v_new, staged, out, b, c, inv_norm, ws, stream);
   }
 }
 
@@ -839,12 +853,13 @@ hipError_t launch_attn_mfma(const PoolGeom& g, const AttnPlan& plan, const void*
   StagedRuns staged{nullptr, nullptr, nullptr, 32};
   if (fresh && hist != nullptr)
     staged = StagedRuns{reinterpret_cast<const uint16_t*>(hist->rows), hist->first_run, hist->run_tok, hist->chunk};
-#define MTS_ATTN_CASE(D_)                                                                                        \
-  case D_:                                                                                                       \
-    if (pw) return fresh ? launch_d<D_, true, true>(g, plan, qp, kp, vp, staged, op, b, c, inv_norm, workspace, stream)   \
-                         : launch_d<D_, true, false>(g, plan, qp, kp, vp, staged, op, b, c, inv_norm, workspace, stream); \
-    return fresh ? launch_d<D_, false, true>(g, plan, qp, kp, vp, staged, op, b, c, 0.f, workspace, stream)               \
-                 : launch_d<D_, false, false>(g, plan, qp, kp, vp, staged, op, b, c, 0.f, workspace, stream);
+#define MTS_ATTN_CASE(D_)                                                                                       \
+  case D_:                                                                                                      \
+    if (pw) return fresh ? launch_d<D_, true, 1>(g, plan, qp, kp, vp, staged, op, b, c, inv_norm, workspace, stream)   \
+                         : launch_d<D_, true, 0>(g, plan, qp, kp, vp, staged, op, b, c, inv_norm, workspace, stream);  \
+    if (staged.first_run) return launch_d<D_, false, 2>(g, plan, qp, kp, vp, staged, op, b, c, 0.f, workspace, stream); \
+    return fresh ? launch_d<D_, false, 1>(g, plan, qp, kp, vp, staged, op, b, c, 0.f, workspace, stream)              \
+                 : launch_d<D_, false, 0>(g, plan, qp, kp, vp, staged, op, b, c, 0.f, workspace, stream);
   switch (g.D) {
     MTS_ATTN_CASE(32)
     MTS_ATTN_CASE(64)

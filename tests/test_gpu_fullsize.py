@@ -112,3 +112,52 @@ def test_unit_values_give_unit_output_everywhere(name, unappended):
         mts.mts_attn_incremental(step.cache.desc, 0, q, out, step.batch.meta, 0.0, step.ws, step.ws_bytes)
     torch.cuda.synchronize()
     assert bool((out == 1.0).all()), f"{name}: {(out != 1.0).sum().item()} of {out.numel()} elements differ from 1"
+
+
+def test_restored_users_attend_from_the_onload_buffer_at_full_size():
+    """host_staging at full size with its restored users' histories left in the onload buffer
+    (mts_attn_incremental_staged, the shape `bench.py --attend-staged` times): the restored users
+    and two cached users, two heads each, against the oracle."""
+    import paper_2604_22881_amd as mts
+    torch, G, w, step = _setup("host_staging")
+    rng = np.random.default_rng([w.seed, 6])
+    miss = [int(u) for u in w.miss_users if w.prefix_lens[u] > 0]
+    hits = [u for u in _sample_users(w, rng, 3) if u not in miss][:2]
+    users = sorted(miss + hits)
+    heads = sorted(rng.choice(w.heads, size=2, replace=False).tolist())
+    H, D = w.heads, w.head_dim
+    data = {"layers": [0], "hist": {0: [None] * w.batch}}
+    for u in users:
+        data["hist"][0][u] = W.normal_elements(rng, (2, int(w.prefix_lens[u]), H, D), w.dtype)
+    for n in ("k_new", "v_new", "q"):
+        data[n] = {0: W.normal_elements(rng, (w.total_new, H, D), w.dtype)}
+    step.unpack_histories(data, 0, users=hits)                 # cached users: in the pool
+    rows, run_tok, first_run = [], [0], np.full(w.batch, -1, np.int32)
+    for u in miss:                                             # restored users: in the onload buffer only
+        first_run[u] = len(run_tok) - 1
+        for start, cnt in W.host_chunks(int(w.prefix_lens[u]), w.chunk_tokens):
+            rows.append(np.ascontiguousarray(data["hist"][0][u][:, start:start + cnt]).reshape(-1))
+            run_tok.append(run_tok[-1] + cnt)
+    q, k, v = (G.to_dev(data[n][0]) for n in ("q", "k_new", "v_new"))
+    out = torch.zeros_like(q)
+    mts.mts_attn_incremental_staged(step.cache.desc, 0, q, k, v, G.to_dev(np.concatenate(rows)),
+                                    torch.from_numpy(first_run).to(G.DEV),
+                                    torch.from_numpy(np.asarray(run_tok, np.int64)).to(G.DEV), w.chunk_tokens, out,
+                                    step.batch.meta, 0.0, step.ws, step.ws_bytes)
+    torch.cuda.synchronize()
+    store = oracle.PagedStore(1, w.num_pages, w.page_size, H, D, w.np_dtype)
+    for u in users:
+        for start, cnt in W.host_chunks(int(w.prefix_lens[u]), w.chunk_tokens):
+            oracle.unpack(store, 0, data["hist"][0][u][:, start:start + cnt], w.user_pages(u), start)
+    oracle.append(store, 0, data["k_new"][0], data["v_new"][0], w.page_indptr, w.page_indices, w.prefix_lens,
+                  w.new_indptr)
+    ref = oracle.attn_incremental(store, 0, data["q"][0], w.page_indptr, w.page_indices, w.prefix_lens, w.new_indptr,
+                                  users=users, heads=heads)
+    gv = as_values(G.to_host(out, w.np_dtype))
+    assert np.isfinite(gv).all()
+    for u in users:
+        lo, hi = int(w.new_indptr[u]), int(w.new_indptr[u + 1])
+        for h in heads:
+            r = ref[lo:hi, h]
+            err = np.abs(gv[lo:hi, h] - r).max()
+            assert err <= 2e-2 * np.abs(r).max(), f"user {u} (P={w.prefix_lens[u]}, staged={u in miss}) head {h}: {err:.3e}"
