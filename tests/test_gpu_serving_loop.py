@@ -13,7 +13,10 @@ import oracle
 pytestmark = pytest.mark.gpu
 
 
-def test_returning_users_over_many_steps_with_eviction_onload_and_offload():
+@pytest.mark.parametrize("order", ["append_first", "deferred_append"])
+def test_returning_users_over_many_steps_with_eviction_onload_and_offload(order):
+    """order: Alg. 1's (append, then attention from the pool), or the attention that reads the
+    step's rows directly with one append of all layers behind the layer loop."""
     import torch
     import gpu_harness as G
     import paper_2604_22881_amd as mts
@@ -76,11 +79,21 @@ def test_returning_users_over_many_steps_with_eviction_onload_and_offload():
                 k = G.to_dev(np.concatenate([r[0] for r in rows])); v = G.to_dev(np.concatenate([r[1] for r in rows]))
                 q = G.to_dev(np.concatenate([r[2] for r in rows]))
                 out = torch.zeros_like(q)
-                mts.mts_kv_append(cache.desc, l, k, v, batch.meta, stream=compute)
+                if order == "append_first":
+                    mts.mts_kv_append(cache.desc, l, k, v, batch.meta, stream=compute)
                 if up:
                     mts.mts_xfer_onload_wait_layer(xfer, l, compute)
-                mts.mts_attn_incremental(cache.desc, l, q, out, batch.meta, 0.0, ws, ws_bytes, stream=compute)
+                if order == "append_first":
+                    mts.mts_attn_incremental(cache.desc, l, q, out, batch.meta, 0.0, ws, ws_bytes, stream=compute)
+                else:
+                    mts.mts_attn_incremental_unappended(cache.desc, l, q, k, v, out, batch.meta, 0.0, ws, ws_bytes,
+                                                        stream=compute)
                 outs.append((k, v, q, out))
+            if order == "deferred_append":
+                k_all = torch.stack([o[0] for o in outs]); v_all = torch.stack([o[1] for o in outs])
+                compute.wait_stream(torch.cuda.current_stream())      # the stacks above ran on the current stream
+                mts.mts_kv_append_layers(cache.desc, 0, L, k_all, v_all, k_all.stride(0) * k_all.element_size(),
+                                         batch.meta, stream=compute)
             cm.commit_batch()
             # persist whole host chunks of the users that are due (Alg. 1 step 9)
             du, dp, dc = cm.offload_due()
