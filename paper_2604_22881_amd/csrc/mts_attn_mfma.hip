@@ -131,7 +131,10 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
   constexpr int KS = D / 32;         // k-steps of Q.K
   constexpr int DB = D / 16;         // 16-dim blocks of the output
 
-  // LDS: per-user metadata and the schedule's prefix sums
+  // LDS: a wavefront-private tile for the V transpose of row tiles (unappended mode), then
+  // per-user metadata and the schedule's prefix sums
+  constexpr int VT_PITCH = D + 8;    // elements per token row of the transpose tile
+  __shared__ __attribute__((aligned(16))) uint16_t vt_tile[FRESH ? kWavesPerWg * kTile * VT_PITCH : 8];
   extern __shared__ int lds[];
   const int B = b.batch;
   int* s_tok = lds;                  // [B+1] new_indptr
@@ -372,23 +375,47 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
           kf[p][hf][s] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(ks, koff + 32 * s * 2, 0, 0));
       }
     };
+    // V rows arrive as they lie in memory, 16 bytes (8 dims of one token) per lane and load:
+    // load j of lane l holds token (64 j + l) / (D/8), dims 8 * ((64 j + l) % (D/8)) .. + 7.
+    // finish_rows() turns them into V^T fragments before the tile is used.
     auto load_rows = [&](auto buf, __amdgpu_buffer_rsrc_t ks, __amdgpu_buffer_rsrc_t vs, int row_first)
         __attribute__((always_inline)) {
       constexpr int p = decltype(buf)::value;
       load_rows_k(buf, ks, row_first);
-      int voff = (row_first + 8 * gq) * row_bytes + r * 2;            // first of this lane's 8 tokens
-      asm volatile("" : "+v"(voff));                   // the 8 row offsets are formed per load, not hoisted
+      int voff = (row_first + lane / (D / 8)) * row_bytes + (lane % (D / 8)) * 16;
+      asm volatile("" : "+v"(voff));
+#pragma unroll
+      for (int j = 0; j < DB; ++j)
+        vf[p][j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(vs, voff + j * (64 / (D / 8)) * row_bytes, 0, 0));
+    };
+    // The transpose of slot p's V rows through the wavefront's LDS tile: rows in, [dim][8 tokens]
+    // fragments out.  Token row t keeps its 16-byte chunks rotated by t / 8, so that the four
+    // lane groups of a fragment read (rows 8 apart) fall on different banks.
+    auto finish_rows = [&](auto buf) __attribute__((always_inline)) {
+      constexpr int p = decltype(buf)::value;
+      constexpr int NCH = D / 8;
+      uint16_t* lt = vt_tile + wave * (kTile * VT_PITCH);
+#pragma unroll
+      for (int j = 0; j < DB; ++j) {
+        const int t = j * (64 / NCH) + lane / NCH, ch = lane % NCH;
+        *reinterpret_cast<u32x4*>(lt + t * VT_PITCH + ((ch + (t >> 3)) % NCH) * 8) = __builtin_bit_cast(u32x4, vf[p][j]);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
+        const int dim = 16 * db + r;
+        const uint16_t* col = lt + (8 * gq) * VT_PITCH + (((dim >> 3) + gq) % NCH) * 8 + (dim & 7);
         uint32_t f[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-          f[e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(vs, voff + e * row_bytes + 32 * db, 0, 0);
+        for (int e = 0; e < 8; ++e) f[e] = col[e * VT_PITCH];
         u32x4 v;
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = f[2 * j] | (f[2 * j + 1] << 16);
         vf[p][db] = __builtin_bit_cast(bf16x8, v);
       }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     };
     // Tile `tile` of a prefix that lies in the onload buffer: the run that holds it (tiles never
     // straddle runs: the run length is a multiple of 32) is its own row source, K plane then V
@@ -579,8 +606,10 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
               for (int tile = t_beg; tile < ring_end; tile += 2) {
                 load_staged(std::integral_constant<int, 1>{}, tile + 1);
                 if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0(tile * kTile);
+                finish_rows(std::integral_constant<int, 0>{});
                 tile_step(nq_c, tail, std::integral_constant<int, 0>{}, tile * kTile);
                 load_staged(std::integral_constant<int, 0>{}, tile + 2);
+                finish_rows(std::integral_constant<int, 1>{});
                 if (tile + 1 < ring_end) tile_step(nq_c, tail, std::integral_constant<int, 1>{}, (tile + 1) * kTile);
               }
             }
@@ -638,6 +667,7 @@ __global__ __launch_bounds__(256, WPS) void attn_stream_kernel(PoolGeom g, Batch
             const int ft = tile - pool_tiles;
             load_rows(std::integral_constant<int, 0>{}, k_rows, v_rows, ft * kTile);
             if (!PW && attempt == 0 && tile == t_beg) reference_from_slot0(P + ft * kTile);
+            finish_rows(std::integral_constant<int, 0>{});
             tile_step(nq_c, tail, std::integral_constant<int, 0>{}, P + ft * kTile);
           }
         }
@@ -777,7 +807,9 @@ hipError_t launch_one(const PoolGeom& g, const AttnPlan& plan, const uint16_t* q
   auto kern = attn_stream_kernel<D, NQB, PF, WPS, PW, SRC>;
   const size_t lds_bytes = sizeof(int) * ((size_t)3 * b.batch + 2 + plan.n_items + 1 + kWavesPerWg);
   static int wgs_per_cu = 0, num_cus = 0;              // per instantiation; same value from any thread
-  static size_t lds_limit = 48 * 1024;
+  // static LDS of the kernel: the V transpose tiles of the unappended forms
+  constexpr size_t static_lds = SRC >= 1 ? (size_t)kWavesPerWg * kTile * (D + 8) * 2 : 64;
+  static size_t lds_limit = 60 * 1024 - static_lds;
   if (wgs_per_cu == 0) {
     int dev = 0, n = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
