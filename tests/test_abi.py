@@ -252,3 +252,39 @@ def test_shapes_beyond_the_schedule_are_refused_not_launched():
     assert _code(mts.mts_attn_incremental, d, 0, FAKE, FAKE, too_many_users, workspace=FAKE, workspace_bytes=1 << 30,
                  stream=0) == B.MTS_ERR_UNSUPPORTED
     assert _code(mts.mts_kv_append, d, 0, FAKE, FAKE, _meta(batch=70000), stream=0) == B.MTS_ERR_INVALID_ARG
+
+
+def test_random_descriptors_and_metadata_never_crash():
+    """Whatever the scalar fields say, every entry point returns a code (or succeeds as a no-op):
+    the host-side checks run before any device work, so this needs no GPU."""
+    rng = np.random.default_rng(4)
+    pick = lambda *v: v[int(rng.integers(0, len(v)))]
+    codes = {B.MTS_ERR_INVALID_ARG, B.MTS_ERR_UNSUPPORTED, B.MTS_ERR_SHAPE, B.MTS_ERR_WORKSPACE, B.MTS_ERR_HIP}
+    for _ in range(400):
+        d = _desc(pool=pick(FAKE, 0, FAKE + 4), layer_stride_bytes=int(pick(1 << 20, 0, -16, 100, 1 << 40)),
+                  dtype=int(pick(B.MTS_BF16, B.MTS_F32, 7, -1)), num_layers=int(pick(2, 0, -3, 1 << 20)),
+                  num_pages=int(pick(8, 0, -1, 1 << 30)), page_size=int(pick(16, 32, 64, 0, 8, 48, -16)),
+                  num_heads=int(pick(4, 0, -2, 1 << 16)), head_dim=int(pick(64, 32, 128, 0, 24, 256, -64)))
+        m = _meta(batch=int(pick(2, 0, -1, 5000, 1 << 30)), page_indptr=pick(FAKE, 0), page_indices=pick(FAKE, 0),
+                  prefix_lens=pick(FAKE, 0), new_indptr=pick(FAKE, 0), total_new=int(pick(10, 0, -5, 1 << 30)),
+                  max_new=int(pick(8, 0, -1, 300, 1 << 30)), max_total_len=int(pick(100, 0, -1, 1 << 30)),
+                  total_pages=int(pick(8, 0, -1, 1 << 30)))
+        layer = int(pick(0, 1, -1, 99))
+        calls = [
+            lambda: mts.mts_page_bytes(d),
+            lambda: mts.mts_attn_workspace_bytes(d, m),
+            lambda: mts.mts_kv_unpack(d, layer, None, 2, None, None, None, 4, m, stream=0),
+            lambda: mts.mts_kv_pack_layers(d, layer, 2, None, 64, 2, None, None, None, 4, m, stream=0),
+            lambda: mts.mts_kv_append(d, layer, None, None, m, stream=0),
+            lambda: mts.mts_kv_append_layers(d, layer, 3, None, None, 64, m, stream=0),
+            lambda: mts.mts_attn_incremental(d, layer, None, None, m, stream=0),
+            lambda: mts.mts_attn_pointwise(d, layer, None, None, m, 0.5, stream=0),
+            lambda: mts.mts_attn_incremental_unappended(d, layer, None, None, None, None, m, stream=0),
+            lambda: mts.mts_attn_incremental_staged(d, layer, None, None, None, None, None, None, 64, None, m, stream=0),
+            lambda: mts.mts_attn_unappended_appends(d, m),
+        ]
+        for call in calls:
+            try:
+                call()                        # no-op shapes (empty batch, nothing to move) succeed
+            except mts.MtsError as e:
+                assert e.code in codes and mts.mts_last_error() != ""
