@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void kv_move_kernel(PoolGeom g, SegDev segs, B
   // 16-token sub-blocks the run covers completely: [full_lo, full_hi) in units of sub-blocks
   const int64_t full_lo = (ppos + 15) >> 4;
   int64_t full_hi = (ppos + npos) >> 4;
-  if (full_hi < full_lo || bulk_blocks == 0) full_hi = full_lo;   // short runs: everything goes group by group
+  if (full_hi < full_lo || bulk_blocks == 0) full_hi = full_lo;   // a launch of short runs: every sub-block takes the masked form
 
   // Which sub-block this wavefront moves, and which of its 16 tokens belong to the run.
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
