@@ -8,10 +8,14 @@ cache-miss users are restored from an HBM-resident staging buffer (mts_kv_unpack
 layer appends the step's K/V rows (mts_kv_append, Alg. 1 step 8.2) and runs its attention over
 the cached prefix plus those rows (mts_attn_incremental, step 8.4), and the users chosen for
 offload are gathered after the layer loop (mts_kv_pack_layers, step 9); all on one stream.
---restore-sync layer selects Alg. 1's stream structure instead (scatter on a side stream with one
-event per layer, step 8.3; gather on the side stream), --deferred-append the attention that
-reads the step's rows directly, with one append of all layers after the loop.  All inputs are
-resident in HBM before the timed region.
+All inputs are resident in HBM before the timed region.
+
+The headline workload is long_history (the KV-read-bound shape); with no --workload the other
+bf16 workloads (batched_incremental, host_staging, miss_prefill) are measured too, each with its
+own step time and roofline, under "configs" of the same line.  For host_staging the line also
+carries the step with the restored users' histories coming from pinned host memory
+(hipMemcpyAsync + mts_kv_unpack per layer on a side stream, one event per layer, Alg. 1 step
+8.3), overlapped and serialised: PCIe-inclusive, never the headline value.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -27,14 +31,18 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+HEADLINE = "long_history"
+OTHERS = ("batched_incremental", "host_staging", "miss_prefill")
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="batched_incremental")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=None,
+                    help=f"time this workload only (default: {HEADLINE} as the headline, the other "
+                         "BASELINE shapes under \"configs\")")
     ap.add_argument("--attention", choices=("softmax", "pointwise"), default="softmax",
                     help="aggregation: mts_attn_incremental (default) or mts_attn_pointwise")
     ap.add_argument("--host-transfer", action="store_true",
@@ -46,6 +54,7 @@ def parse():
                          "manager + transfer pipeline + kernels) and through full recompute; adds a "
                          "\"serving_trace\" object to the line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-pcie", action="store_true", help="skip the pinned-host legs of host_staging")
     ap.add_argument("--eager", action="store_true", help="enqueue every step call by call instead of replaying a HIP graph")
     ap.add_argument("--deferred-append", action="store_true",
                     help="the attention takes the step's K/V rows from k_new / v_new itself "
@@ -60,10 +69,7 @@ def parse():
                     help="restored users' staged histories (already in HBM here): 'step' scatters all layers with "
                          "one launch ahead of layer 0 and gathers the offload after the appends, all on one stream; "
                          "'layer' scatters on a side stream layer by layer with one event each and gathers there "
-                         "too (Alg. 1 steps 8.3 and 9: what a restore arriving over PCIe needs, see --host-transfer)")
-    ap.add_argument("--pack-per-layer", action="store_true",
-                    help="diagnostic: gather layer l's evicted runs right after layer l's append, concurrently "
-                         "with its attention, instead of after the layer loop")
+                         "too (Alg. 1 steps 8.3 and 9)")
     ap.add_argument("--no-miss", action="store_true", help="diagnostic: no restored users (no unpack, no per-layer wait)")
     ap.add_argument("--no-evict", action="store_true", help="diagnostic: no packed users")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -85,18 +91,16 @@ def attention_flops_per_layer(w):
     return 4 * w.head_dim * w.heads * pairs
 
 
-def cpu_baseline(w, budget_s=12.0, pointwise=False):
-    """The oracle, as it stands, on a bounded sample of the same workload: whole users (all
-    heads), one layer's worth of work per pass - unpack of the history in host-chunk runs,
-    append, attention - repeated over fresh data until about `budget_s` seconds of CPU work."""
+def spread(ms):
+    import numpy as np
+    a = np.asarray(ms, dtype=np.float64)
+    return {"median": float(np.median(a)), "p10": float(np.percentile(a, 10)), "p90": float(np.percentile(a, 90))}
+
+
+def _oracle_passes(w, budget_s, pointwise):
     import numpy as np
     import oracle
     import mts_workloads as W
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        threads = 1
     rng = np.random.default_rng([w.seed, 99])
     layer_tokens, t_used, passes = 0, 0.0, 0
     while t_used < budget_s:
@@ -120,12 +124,53 @@ def cpu_baseline(w, budget_s=12.0, pointwise=False):
         t_used += time.perf_counter() - t0
         layer_tokens += n
         passes += 1
+    return layer_tokens, t_used, passes
+
+
+def cpu_baseline(w, budget_s=10.0, budget_1core_s=8.0, pointwise=False):
+    """The oracle, as it stands, on a bounded sample of the same workload: whole users (all
+    heads), one layer's worth of work per pass - unpack of the history in host-chunk runs,
+    append, attention - repeated over fresh data until about `budget_s` seconds of CPU work; then
+    the same with the numerical library held to one thread."""
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+        import numpy  # noqa: F401  (loads the BLAS the info call reports)
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threadpool_limits, threads = None, 1
+    layer_tokens, t_used, passes = _oracle_passes(w, budget_s, pointwise)
     # a step runs all layers over the same new tokens: new tokens/s = (token x layer) rate / layers
-    value = layer_tokens / t_used / w.layers
-    return {"value": value, "unit": "new_tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{passes} (user, layer) passes over the workload's users in order, whole histories, all "
-                      f"heads: unpack + append + attention in fp64, {t_used:.1f} s of CPU work; rate divided by "
-                      f"the {w.layers} layers of a step"}
+    res = {"value": layer_tokens / t_used / w.layers, "unit": "new_tokens/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"{passes} (user, layer) passes over the workload's users in order, whole histories, all "
+                     f"heads: unpack + append + attention in fp64, {t_used:.1f} s of CPU work; rate divided by "
+                     f"the {w.layers} layers of a step"}
+    if threadpool_limits is not None and budget_1core_s > 0:
+        with threadpool_limits(limits=1):
+            lt1, t1, p1 = _oracle_passes(w, budget_1core_s, pointwise)
+        res["value_1core"] = lt1 / t1 / w.layers
+        res["sample_1core"] = f"{p1} passes, {t1:.1f} s, numerical library held to one thread"
+    return res
+
+
+def read_ceiling(dev, mts, torch, compute, gib=2, reps=10):
+    """A plain streaming read (mts_diag_stream_read) over a buffer far larger than any cache: what a
+    kernel that only issues 16-byte loads reaches on this machine, in GB/s."""
+    n = gib << 30
+    buf = torch.empty(n, dtype=torch.uint8, device=dev)
+    buf.view(torch.int32).fill_(3)
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for _ in range(2):
+        mts.mts_diag_stream_read(buf, n, sink, stream=compute)
+    for a, b in evs:
+        a.record(compute)
+        mts.mts_diag_stream_read(buf, n, sink, stream=compute)
+        b.record(compute)
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in evs]
+    sp = spread(ms)
+    return {"kernel": "mts_diag_stream_read", "bytes": n, "gbps_median": n / (sp["median"] * 1e-3) / 1e9,
+            "gbps_best": n / (min(ms) * 1e-3) / 1e9, "frac_of_peak": n / (sp["median"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
 
 
 def host_transfer_leg(args, w, cache, batch, miss_segs, evict_segs, q, k_new, v_new, out, ws, ws_bytes, compute,
@@ -256,6 +301,7 @@ def serving_trace_leg(w, compute, n_users=512, batch=16, warm_steps=60, steps=12
     tally = dict(requests=0, new_tokens=0, onload_tokens=0, offload_tokens=0, steps_refused=0, offload_refused=0,
                  t_metadata=0.0, t_onload_wait=0.0, t_gpu_tail=0.0)
     times, sampled = [], []
+    in_flight = []      # (segments, host runs, batch) of offload tasks that may still be running
     try:
         for step in range(warm_steps + steps):
             timed = step >= warm_steps
@@ -295,24 +341,34 @@ def serving_trace_leg(w, compute, n_users=512, batch=16, warm_steps=60, steps=12
             du, dp, dc = cm.offload_due()
             if len(du):
                 local = {int(u): i for i, u in enumerate(users)}
+                # a user left due by an earlier refused task may not be in this batch: its page list is
+                # not in this step's metadata, so it stays due (and locked) until it returns
+                due = [(u, p, c) for u, p, c in zip(du.tolist(), dp.tolist(), dc.tolist())]
                 su, sp, sc = [], [], []
-                for u, p, c in zip(du.tolist(), dp.tolist(), dc.tolist()):
-                    for a in range(p, p + c, chunk):
-                        su.append(local[u]); sp.append(a); sc.append(chunk)
-                osegs = SegmentList(su, sp, sc, dev)
-                off_host = HostRuns(osegs, host_arrays(host_dst, sc))
-                try:
-                    mts.mts_xfer_offload_submit(xfer, cache.desc, bm.meta, off_host.runs, compute)
-                    ok = True
-                except mts.MtsError as e:
-                    if e.code != mts.MTS_ERR_BUSY:
-                        raise
-                    ok = False
-                    tally["offload_refused"] += 1
-                for u, p, c in zip(du.tolist(), dp.tolist(), dc.tolist()):
-                    cm.offload_done(u, p + c if ok else p)        # marked persisted at submission (timing run)
-                    if ok and timed:
+                for u, p, c in due:
+                    if u in local:
+                        for a in range(p, p + c, chunk):
+                            su.append(local[u]); sp.append(a); sc.append(chunk)
+                ok = False
+                if su:
+                    osegs = SegmentList(su, sp, sc, dev)
+                    off_host = HostRuns(osegs, host_arrays(host_dst, sc))
+                    try:
+                        mts.mts_xfer_offload_submit(xfer, cache.desc, bm.meta, off_host.runs, compute)
+                        ok = True
+                        # the task reads these device arrays until it has finished: keep them alive
+                        in_flight.append((osegs, off_host, bm))
+                    except mts.MtsError as e:
+                        if e.code != mts.MTS_ERR_BUSY:
+                            raise
+                        tally["offload_refused"] += 1
+                for u, p, c in due:
+                    done = ok and u in local
+                    cm.offload_done(u, p + c if done else p)      # marked persisted at submission (timing run)
+                    if done and timed:
                         tally["offload_tokens"] += c
+            if in_flight and mts.mts_xfer_offload_pending_tokens(xfer) == 0:
+                in_flight.clear()                                  # every submitted task has finished
             ts = time.perf_counter()
             compute.synchronize()                                  # the requests' outputs are ready
             if timed:
@@ -328,6 +384,7 @@ def serving_trace_leg(w, compute, n_users=512, batch=16, warm_steps=60, steps=12
             if step == warm_steps - 1:
                 base = cm.stats()
         mts.mts_xfer_drain(xfer)
+        in_flight.clear()
         st = cm.stats()
     finally:
         mts.mts_xfer_destroy(xfer)
@@ -376,29 +433,150 @@ def serving_trace_leg(w, compute, n_users=512, batch=16, warm_steps=60, steps=12
                     "figures are not a speed-up"}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
-              "(the path shards by user, with no exchange step between GPUs)", file=sys.stderr)
-        sys.exit(2)
+
+
+def sub_batch(w, users, dev):
+    """DeviceBatch of a subset of the workload's users (their page lists, lengths and a ragged
+    offset array over their own rows)."""
+    import numpy as np
+    from paper_2604_22881_amd.runtime import DeviceBatch
+    users = [int(u) for u in users]
+    pages = [w.user_pages(u) for u in users]
+    indptr = np.concatenate([[0], np.cumsum([len(p) for p in pages])]).astype(np.int32)
+    indices = np.concatenate(pages).astype(np.int32) if pages else np.zeros(0, np.int32)
+    new = np.asarray([w.new_lens[u] for u in users], dtype=np.int32)
+    new_indptr = np.concatenate([[0], np.cumsum(new)]).astype(np.int32)
+    prefix = np.asarray([w.prefix_lens[u] for u in users], dtype=np.int32)
+    return DeviceBatch(indptr, indices, prefix, new_indptr, dev), int(new_indptr[-1])
+
+
+def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
+    """host_staging with the link in the loop (Sec. 4.2, Sec. 4.4, Alg. 1 step 8.3): the restored
+    users' histories lie in pinned host memory in host-chunk runs.  Overlapped: per layer, the side
+    stream copies the layer's runs to the onload buffer (hipMemcpyAsync), scatters them
+    (mts_kv_unpack) and records an event; the compute stream runs the other users' append +
+    attention of that layer, waits for the event, then runs the restored users'.  Serialised: the
+    same calls on one stream, copies first.  Eager launches; PCIe-inclusive."""
+    import numpy as np
+    import torch
+    import paper_2604_22881_amd as mts
+    from paper_2604_22881_amd.runtime import SegmentList
+    dev = cache.device
+    L, H, D = w.layers, w.heads, w.head_dim
+    miss = [int(u) for u in w.miss_users if w.prefix_lens[u] > 0]
+    hit = [u for u in range(w.batch) if u not in set(miss)]
+    hit_b, n_hit = sub_batch(w, hit, dev)
+    miss_b, n_miss = sub_batch(w, miss, dev)
+    segs = SegmentList.for_histories(list(range(len(miss))), [w.prefix_lens[u] for u in miss], w.chunk_tokens, dev)
+    layer_elems = segs.total_tokens * 2 * H * D
+    layer_bytes = layer_elems * 2
+    pinned = torch.empty(L, layer_elems, dtype=torch.bfloat16, pin_memory=True)
+    pinned.normal_()
+    staging = torch.empty(L, layer_elems, dtype=torch.bfloat16, device=dev)
+    evict = [int(u) for u in w.evict_users]
+    full_b, _ = sub_batch(w, list(range(w.batch)), dev)
+    evict_segs = SegmentList.for_histories(evict, [w.total_lens[u] for u in evict], w.chunk_tokens, dev)
+    offload = torch.empty(L, max(evict_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
+    off_stride = offload.stride(0) * 2
+    ws_bytes = max(mts.mts_attn_workspace_bytes(cache.desc, hit_b.meta), mts.mts_attn_workspace_bytes(cache.desc, miss_b.meta))
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    ev = [torch.cuda.Event() for _ in range(L)]
+    ev_start = torch.cuda.Event()
+    cs, ss = compute.cuda_stream, side.cuda_stream
+
+    def layer_work(l, b, lo, hi):
+        mts.mts_kv_append(cache.desc, l, k_new[l][lo:hi], v_new[l][lo:hi], b.meta, stream=cs)
+        mts.mts_attn_incremental(cache.desc, l, q[l][lo:hi], out[l][lo:hi], b.meta, 0.0, ws, ws_bytes, stream=cs)
+
+    def step(overlap):
+        xs = ss if overlap else cs
+        if overlap:
+            ev_start.record(compute)
+            side.wait_event(ev_start)                  # the onload buffer is free once the last step is over
+        for l in range(L):
+            mts.mts_stage_h2d_async(staging[l], pinned[l], layer_bytes, stream=xs)
+            mts.mts_kv_unpack(cache.desc, l, staging[l], *segs.args(), miss_b.meta, stream=xs)
+            if overlap:
+                ev[l].record(side)
+        for l in range(L):
+            layer_work(l, hit_b, 0, n_hit)
+            if overlap:
+                compute.wait_event(ev[l])              # Alg. 1 step 8.3
+            layer_work(l, miss_b, n_hit, n_hit + n_miss)
+        if evict_segs.num_segs:
+            mts.mts_kv_pack_layers(cache.desc, 0, L, offload, off_stride, *evict_segs.args(), full_b.meta, stream=cs)
+
+    def timed(overlap):
+        for _ in range(3):
+            step(overlap)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(overlap)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    t_over = timed(True)
+    t_ser = timed(False)
+    # the transfer alone, in the per-layer pieces the step uses, and as one plain copy of the same bytes
+    def copy_only(per_layer):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            if per_layer:
+                for l in range(L):
+                    mts.mts_stage_h2d_async(staging[l], pinned[l], layer_bytes, stream=ss)
+            else:
+                mts.mts_stage_h2d_async(staging, pinned, L * layer_bytes, stream=ss)
+        side.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+    copy_only(True)
+    t_h2d = copy_only(True)
+    t_plain = copy_only(False)
+    # the same two-batch step with the staged histories already in HBM (no copy): what is left to hide
+    def no_copy_step():
+        mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, layer_bytes, *segs.args(), miss_b.meta, stream=cs)
+        for l in range(L):
+            layer_work(l, hit_b, 0, n_hit)
+            layer_work(l, miss_b, n_hit, n_hit + n_miss)
+        if evict_segs.num_segs:
+            mts.mts_kv_pack_layers(cache.desc, 0, L, offload, off_stride, *evict_segs.args(), full_b.meta, stream=cs)
+    for _ in range(3):
+        no_copy_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        no_copy_step()
+    torch.cuda.synchronize()
+    t_split = (time.perf_counter() - t0) * 1e3 / steps
+    transfer_ms = max(t_ser - t_split, 1e-9)
+    return {"ms_per_step_overlapped": t_over, "ms_per_step_serialised": t_ser,
+            "ms_per_step_two_batches_staging_in_hbm": t_split, "ms_per_step_staging_in_hbm_one_batch_graph": resident_ms,
+            "h2d_bytes_per_step": L * layer_bytes, "h2d_ms_per_step_alone": t_h2d,
+            "h2d_gbps": L * layer_bytes / (t_h2d * 1e-3) / 1e9,
+            "plain_pinned_copy_gbps": L * layer_bytes / (t_plain * 1e-3) / 1e9,
+            "fraction_of_transfer_hidden": max(0.0, min(1.0, (t_ser - t_over) / transfer_ms)),
+            "restored_users": len(miss), "steps": steps, "launch": "eager",
+            "note": "pinned host -> hipMemcpyAsync -> mts_kv_unpack per layer on a side stream, one event per layer; "
+                    "other users' attention runs meanwhile, restored users' after the event; PCIe-inclusive, "
+                    "never the headline value"}
+
+
+def bench_workload(args, name, steps, warmup, extras):
+    """Times `steps` steps of one workload; returns the fields of its result."""
     import numpy as np
     import torch
     import mts_workloads as W
     import paper_2604_22881_amd as mts
     from paper_2604_22881_amd.runtime import DeviceBatch, PagedKVCache, SegmentList
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    w = W.make_workload(args.workload)
+    w = W.make_workload(name)
     assert w.dtype == "bf16", "the benchmark workloads are bf16"
     L, H, D = w.layers, w.heads, w.head_dim
     torch.manual_seed(w.seed)
 
-    if args.calibrate_copy:
+    if args.calibrate_copy and extras:
         cal_src = torch.empty(256 << 20, dtype=torch.int32, device=dev).fill_(7)
     # ---- inputs, resident in HBM before timing ------------------------------------------
     cache = PagedKVCache(L, w.num_pages, w.page_size, H, D, w.dtype, dev)
@@ -433,10 +611,8 @@ def main():
 
     # Default: Alg. 1's order, layer by layer - 8.2 append, then 8.4 attention reads the rows back from
     # the pool.  --deferred-append: the attention takes the step's rows from k_new / v_new itself and
-    # every layer's rows are written to the pool by ONE launch after the layer loop (a serving engine
-    # keeps the L small row buffers of a step alive until then), so no copy sits between two layers'
-    # attentions.  Long new segments (read from the pool by the dense-prefill kernel) always keep
-    # Alg. 1's order.
+    # every layer's rows are written to the pool by ONE launch after the layer loop.  Long new segments
+    # (read from the pool by the dense-prefill kernel) always keep Alg. 1's order.
     deferred_append = ((args.deferred_append or args.attend_staged)
                        and not mts.mts_attn_unappended_appends(cache.desc, batch.meta))
     attend_staged = args.attend_staged and deferred_append and miss_segs.num_segs > 0 and not pointwise
@@ -453,8 +629,7 @@ def main():
     # 'layer': the paper's stream structure - scatter on the side stream with one event per layer that
     # the layer's attention waits for (Alg. 1 step 8.3), offload gathered on the side stream behind the
     # appends (step 9).  'step': the staged histories are already in HBM, so nothing is gained by
-    # pipelining them layer by layer; scatter, attention, append and gather follow one another on one
-    # stream and no cross-stream dependency (several microseconds each) sits between two layers.
+    # pipelining them layer by layer; everything follows on one stream.
     per_layer = args.restore_sync == "layer"
     xs = ss if per_layer else cs                          # stream of the scatter and the gather
 
@@ -469,7 +644,6 @@ def main():
             mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride, *miss_segs.args(), batch.meta, stream=cs)
         for l in range(L):
             if append_first:
-                # Alg. 1's order: 8.2 append, then 8.4 attention reads the rows back from the pool
                 mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs)
             if miss_segs.num_segs and per_layer and not attend_staged:
                 compute.wait_event(ev_unpacked[l])
@@ -493,15 +667,11 @@ def main():
                                                     ws, ws_bytes, stream=cs)
             if attn_events is not None:
                 b.record(compute)
-            if evict_segs.num_segs and args.pack_per_layer and not deferred_append:
-                ev_appended[l].record(compute)
-                side.wait_event(ev_appended[l])
-                mts.mts_kv_pack(cache.desc, l, offload[l], *evict_segs.args(), batch.meta, stream=ss)
         if attend_staged:
             mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride, *miss_segs.args(), batch.meta, stream=cs)
         if deferred_append:
             mts.mts_kv_append_layers(cache.desc, 0, L, k_new, v_new, rows_stride, batch.meta, stream=cs)
-        if evict_segs.num_segs and not (args.pack_per_layer and not deferred_append):
+        if evict_segs.num_segs:
             # Alg. 1 step 9: the offload is submitted after the layer loop, behind the last append;
             # every layer's runs are gathered by one launch
             if per_layer:
@@ -509,17 +679,18 @@ def main():
                 side.wait_event(ev_appended[L - 1])
             mts.mts_kv_pack_layers(cache.desc, 0, L, offload, offload_stride, *evict_segs.args(), batch.meta, stream=xs)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
 
-    K = args.steps
+    K = steps
     if args.eager:
-        run_step = step
+        def run_step():
+            step()
     else:
-        # The step is launch-bound on the host (about ten enqueue calls per layer against
-        # tens of microseconds of GPU work), so it is captured once into a HIP graph - both
-        # streams, forked and joined by events - and replayed.
+        # The step is launch-bound on the host (a few enqueue calls per layer against tens of
+        # microseconds of GPU work), so it is captured once into a HIP graph - both streams, forked and
+        # joined by events - and replayed.
         graph = torch.cuda.CUDAGraph()
         ev_fork, ev_join = torch.cuda.Event(), torch.cuda.Event()
         with torch.cuda.graph(graph, stream=compute):
@@ -528,7 +699,10 @@ def main():
             step()
             ev_join.record(side)
             compute.wait_event(ev_join)
-        run_step = graph.replay
+
+        def run_step():
+            with torch.cuda.stream(compute):
+                graph.replay()
         for _ in range(3):
             run_step()
     torch.cuda.synchronize()
@@ -537,6 +711,16 @@ def main():
         run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+
+    # The same K steps again, each bracketed by HIP events on the compute stream: the spread.
+    step_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    for a, b in step_ev:
+        a.record(compute)
+        run_step()
+        b.record(compute)
+    torch.cuda.synchronize()
+    step_ms = [a.elapsed_time(b) for a, b in step_ev]
 
     # Duration of the dominant kernel: HIP events on the compute stream around every
     # attention launch of K more (eager) steps of the same work.
@@ -546,14 +730,13 @@ def main():
         step(attn_ev[s])
     torch.cuda.synchronize()
 
-    if args.calibrate_copy:
+    if args.calibrate_copy and extras:
         # cal_src was filled before all the work above, so none of it is left in any cache
         cal_dst = torch.empty_like(cal_src)
         torch.cuda.synchronize()
         cal_dst.copy_(cal_src)                           # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
 
-    ms_per_step = (t1 - t0) * 1e3 / K
     attn_ms = [a.elapsed_time(b) for evs in attn_ev for (a, b) in evs]
     attn_ms_avg = float(np.mean(attn_ms))
     kv_bytes, qo_bytes = algorithmic_bytes_per_layer(w)
@@ -562,12 +745,9 @@ def main():
     flops = attention_flops_per_layer(w)
 
     res = {
-        "metric": "new tokens/sec + KV-read HBM GB/s (% of peak) for cached-prefix incremental attention",
-        "value": N / (ms_per_step * 1e-3),
-        "unit": "new_tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic", "launch": "eager" if args.eager else "hip_graph",
+        "value": N / (ms_per_step * 1e-3), "unit": "new_tokens/s",
+        "steps": K, "warmup": warmup, "ms_per_step": ms_per_step, "ms_per_step_events": spread(step_ms),
+        "launch": "eager" if args.eager else "hip_graph",
         "restore_sync": args.restore_sync, "attend_staged": bool(attend_staged),
         "append": "all layers in one launch after the layer loop" if deferred_append else "per layer, before the attention",
         "config": {"workload": w.name, "seed": w.seed, "users": w.batch, "layers": L, "heads": H,
@@ -577,8 +757,9 @@ def main():
         "kv_read_gbps_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9,
         "kv_read_frac_of_peak_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "attention_tflops": flops / (attn_ms_avg * 1e-3) / 1e12,
+        "attention_launch_ms": spread(attn_ms),
         "roofline": {"kernel": ("mts_attn_pointwise" if pointwise else "mts_attn_incremental") +
-                               ("_unappended" if deferred_append else "") + " (attention kernel + split-kv merge)",
+                               ("_unappended" if deferred_append else "") + " (one launch = one layer of the batch)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "bytes_per_launch": alg_bytes, "avg_launch_ms": attn_ms_avg},
@@ -594,11 +775,52 @@ def main():
     if os.path.exists(traffic_file) and not pointwise:          # measured HBM bytes per launch, from rocprofv3 --pmc runs
         with open(traffic_file) as f:
             res["roofline"]["traffic"] = json.load(f).get("hbm_bytes_per_launch")
-    if args.host_transfer and miss_segs.num_segs:
-        res["transfer"] = host_transfer_leg(args, w, cache, batch, miss_segs, evict_segs, q, k_new, v_new, out, ws,
-                                            ws_bytes, compute, pointwise, inv_norm)
-    if args.serving_trace:
-        res["serving_trace"] = serving_trace_leg(w, compute)
+    if name == "host_staging" and not args.no_pcie and not pointwise and len(w.miss_users):
+        res["pcie"] = pcie_leg(w, cache, q, k_new, v_new, out, compute, side, max(10, K // 4), ms_per_step)
+    if extras:
+        if args.host_transfer and miss_segs.num_segs:
+            res["transfer"] = host_transfer_leg(args, w, cache, batch, miss_segs, evict_segs, q, k_new, v_new, out, ws,
+                                                ws_bytes, compute, pointwise, inv_norm)
+        if args.serving_trace:
+            res["serving_trace"] = serving_trace_leg(w, compute)
+        res["_workload"] = w
+        res["_compute"] = compute
+    del cache, q, k_new, v_new, out, ws, staging, offload
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
+              "(the path shards by user, with no exchange step between GPUs)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2604_22881_amd as mts
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    pointwise = args.attention == "pointwise"
+
+    head_name = args.workload or HEADLINE
+    head = bench_workload(args, head_name, args.steps, args.warmup, extras=True)
+    w, compute = head.pop("_workload"), head.pop("_compute")
+    res = {"metric": "new tokens/sec + KV-read HBM GB/s (% of peak) for cached-prefix incremental attention",
+           "value": head.pop("value"), "unit": head.pop("unit"), "n_gpus": 1,
+           "steps": head.pop("steps"), "warmup": head.pop("warmup"), "ms_per_step": head.pop("ms_per_step"),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    res.update(head)
+    if args.workload is None:
+        # the other BASELINE shapes, each with its own step time and roofline
+        res["configs"] = {}
+        for name in OTHERS:
+            k = max(10, min(args.steps, 50 if name != "miss_prefill" else 20))
+            r = bench_workload(args, name, k, max(2, min(args.warmup, 5)), extras=False)
+            res["configs"][name] = r
+    res["hbm_read_ceiling"] = read_ceiling("cuda:0", mts, torch, compute)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, pointwise=pointwise)
     print(json.dumps(res))

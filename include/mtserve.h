@@ -417,6 +417,14 @@ int32_t mts_cm_set_locked(mts_cm* m, int64_t user, int32_t locked);
 int64_t mts_cm_take_evicted(mts_cm* m, int64_t* users, int64_t capacity);
 int32_t mts_cm_get_stats(mts_cm* m, mts_cm_stats* out);
 
+/*
+ * Measurement yardstick (not part of the method): reads `bytes` bytes of device memory at `src`
+ * once, 16 bytes per lane, and folds them into `sink` (device, 4096 bytes, any contents).  Timed
+ * by the caller, it gives the rate a kernel that only streams reaches on this machine, which is
+ * what the attention kernels' HBM fractions are to be read against.  src and bytes multiples of 16.
+ */
+int32_t mts_diag_stream_read(const void* src, int64_t bytes, void* sink, void* stream);
+
 /* Text of the calling thread's last error ("" if none).  Never NULL. */
 const char* mts_last_error(void);
 

@@ -24,7 +24,7 @@ EXPORTS = (
     "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_pointwise",
     "mts_attn_unappended_appends", "mts_attn_incremental_unappended", "mts_attn_pointwise_unappended",
     "mts_attn_incremental_staged",
-    "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_last_error", "mts_version",
+    "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_diag_stream_read", "mts_last_error", "mts_version",
     "mts_xfer_create", "mts_xfer_destroy", "mts_xfer_onload_submit", "mts_xfer_onload_wait_layer",
     "mts_xfer_offload_submit", "mts_xfer_offload_pending_tokens", "mts_xfer_drain",
     "mts_cm_create", "mts_cm_destroy", "mts_cm_import_history", "mts_cm_cached_length", "mts_cm_prepare_batch", "mts_cm_commit_batch",
@@ -100,6 +100,7 @@ def lib():
         "mts_attn_incremental_staged": (I32, [DESC, I32, P, P, P, P, P, P, I32, P, META, F32, P, I64, P]),
         "mts_stage_h2d_async": (I32, [P, P, I64, P]),
         "mts_stage_d2h_async": (I32, [P, P, I64, P]),
+        "mts_diag_stream_read": (I32, [P, I64, P, P]),
         "mts_xfer_create": (I32, [C.POINTER(XferConfig), C.POINTER(P)]),
         "mts_xfer_destroy": (I32, [P]),
         "mts_xfer_onload_submit": (I32, [P, DESC, META, C.POINTER(XferRuns), P, I64]),
@@ -365,3 +366,7 @@ def mts_stage_h2d_async(device_dst, host_src, nbytes, stream=None):
 
 def mts_stage_d2h_async(host_dst, device_src, nbytes, stream=None):
     return _check(lib().mts_stage_d2h_async(_ptr(host_dst), _ptr(device_src), int(nbytes), _stream(stream)))
+
+
+def mts_diag_stream_read(src, nbytes, sink, stream=None):
+    return _check(lib().mts_diag_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)))

@@ -1,6 +1,6 @@
 """Builds libmtserve_hip.so (gfx950) in-tree with hipcc.
 
-    python -m paper_2604_22881_amd.build
+    python -m paper_2604_22881_amd.build [--incremental]
 """
 from __future__ import annotations
 
@@ -27,8 +27,17 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def _compile(src: str) -> str:
+def _newest_header() -> float:
+    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    hdrs.append(os.path.join(PKG_DIR, "..", "include", "mtserve.h"))
+    return max(os.path.getmtime(h) for h in hdrs)
+
+
+def _compile(src: str, incremental: bool = False) -> str:
     obj = os.path.join(BUILD_DIR, src.replace(".hip", ".o"))
+    if incremental and os.path.exists(obj) and \
+            os.path.getmtime(obj) > max(os.path.getmtime(os.path.join(CSRC, src)), _newest_header()):
+        return obj
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -40,10 +49,11 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(jobs: int = 4) -> str:
+def build_library(jobs: int = 4, incremental: bool = False) -> str:
+    """Compiles every source (with `incremental`, only those newer than their object) and links."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, sources()))
+        objs = list(ex.map(lambda s: _compile(s, incremental), sources()))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB_PATH, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -52,4 +62,4 @@ def build_library(jobs: int = 4) -> str:
 
 
 if __name__ == "__main__":
-    print(build_library())
+    print(build_library(incremental="--incremental" in sys.argv))
