@@ -201,6 +201,24 @@ int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const v
                              void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * mts_attn_incremental for callers that cannot allocate device memory or hand over a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, arguments, preconditions and results as mts_attn_incremental, but the split-kv
+ * partials live in a buffer the library owns: a file-scope device array of
+ * MTS_NOALLOC_SCRATCH_BYTES, one copy on every GPU the library is loaded on, held until the
+ * process ends.  The call allocates and frees nothing.  Shapes whose workspace
+ * (mts_attn_workspace_bytes) exceeds that size are refused with MTS_ERR_WORKSPACE before anything
+ * is launched.  All calls on one GPU share the one buffer: calls that overlap in time on the same
+ * GPU (different streams, different host threads) race and give wrong results; calls ordered on
+ * one stream are safe.  The first call on a device looks the buffer's address up in the runtime:
+ * make it outside stream capture.
+ */
+#define MTS_NOALLOC_SCRATCH_BYTES (40ll << 20)
+int32_t mts_attn_incremental_noalloc(const mts_cache_desc* cache, int32_t layer, const void* q,
+                                     void* out, const mts_batch_meta* meta, float sm_scale,
+                                     void* stream);
+
+/*
  * Pointwise-aggregated variant of mts_attn_incremental: the same queries, keys, visibility and
  * paged reads, with the aggregation of the HSTU-style backbone the paper serves (Sec. 2, Eq. 1-3;
  * the paper prints no formula for its Attention, so this header states the one computed):

@@ -21,7 +21,7 @@ MTS_F32, MTS_BF16 = 0, 1
 EXPORTS = (
     "mts_page_bytes", "mts_pages_for", "mts_elem_offset", "mts_kv_unpack", "mts_kv_pack",
     "mts_kv_unpack_layers", "mts_kv_pack_layers", "mts_kv_append_layers",
-    "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_pointwise",
+    "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_incremental_noalloc", "mts_attn_pointwise",
     "mts_attn_unappended_appends", "mts_attn_incremental_unappended", "mts_attn_pointwise_unappended",
     "mts_attn_incremental_staged",
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_diag_stream_read", "mts_last_error", "mts_version",
@@ -93,6 +93,7 @@ def lib():
         "mts_kv_append_layers": (I32, [DESC, I32, I32, P, P, I64, META, P]),
         "mts_attn_workspace_bytes": (I64, [DESC, META]),
         "mts_attn_incremental": (I32, [DESC, I32, P, P, META, F32, P, I64, P]),
+        "mts_attn_incremental_noalloc": (I32, [DESC, I32, P, P, META, F32, P]),
         "mts_attn_pointwise": (I32, [DESC, I32, P, P, META, F32, F32, P, I64, P]),
         "mts_attn_unappended_appends": (I32, [DESC, META]),
         "mts_attn_incremental_unappended": (I32, [DESC, I32, P, P, P, P, META, F32, P, I64, P]),
@@ -226,6 +227,14 @@ def mts_attn_incremental(desc, layer, q, out, meta, sm_scale=0.0, workspace=None
     return _check(lib().mts_attn_incremental(C.byref(desc), layer, _ptr(q), _ptr(out), C.byref(meta),
                                              float(sm_scale), _ptr(workspace), int(workspace_bytes),
                                              _stream(stream)))
+
+
+MTS_NOALLOC_SCRATCH_BYTES = 40 << 20
+
+
+def mts_attn_incremental_noalloc(desc, layer, q, out, meta, sm_scale=0.0, stream=None):
+    return _check(lib().mts_attn_incremental_noalloc(C.byref(desc), layer, _ptr(q), _ptr(out), C.byref(meta),
+                                                     float(sm_scale), _stream(stream)))
 
 
 def mts_attn_pointwise(desc, layer, q, out, meta, inv_norm, sm_scale=0.0, workspace=None, workspace_bytes=0,

@@ -5,6 +5,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/mtserve.h"
 #include "mts_internal.hpp"
 
@@ -114,6 +116,38 @@ int32_t hip_status(hipError_t e, const char* what) {
 }
 
 int64_t roundup(int64_t v, int m) { return (v + m - 1) / m * m; }
+
+// ---- library-owned scratch of mts_attn_incremental_noalloc -----------------------------------
+// One copy per GPU the library is loaded on, held until the process ends.  In host code the
+// array's name is only a stand-in for the symbol: the memory's address on the current device is
+// asked from the runtime once per device and kept.
+constexpr int64_t kScratchBytes = MTS_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device; nullptr + error text on failure
+void* scratch_on_current_device() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(MTS_ERR_HIP, "hipGetDevice: %s (device %d)", hipGetErrorString(e), dev);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      fail(MTS_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 }  // namespace
 
@@ -392,6 +426,27 @@ int32_t mts_attn_incremental(const mts_cache_desc* cache, int32_t layer, const v
                              int64_t workspace_bytes, void* stream) {
   return attention_call("mts_attn_incremental launch", cache, layer, q, out, meta, sm_scale, 0.f, workspace,
                         workspace_bytes, stream);
+}
+
+int32_t mts_attn_incremental_noalloc(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
+                                     const mts_batch_meta* meta, float sm_scale, void* stream) {
+  // the shape's needs are known from the host-side bounds alone: refuse before touching the device
+  mts::PoolGeom g{};
+  mts::BatchDev b{};
+  int32_t st;
+  if ((st = check_cache(cache, layer, true, &g)) != MTS_OK) return st;
+  if ((st = check_meta(meta, true, true, &b)) != MTS_OK) return st;
+  const mts::AttnPlan plan = mts::plan_attention(g, b);
+  if (plan.too_large) return fail(MTS_ERR_UNSUPPORTED, "too many query tiles or kv tiles for one call");
+  if (plan.ws_bytes > kScratchBytes)
+    return fail(MTS_ERR_WORKSPACE, "this shape needs %lld bytes of scratch, the library-owned buffer of "
+                "mts_attn_incremental_noalloc holds %lld: use mts_attn_incremental with a workspace",
+                (long long)plan.ws_bytes, (long long)kScratchBytes);
+  if (b.batch == 0 || b.total_new == 0) return MTS_OK;
+  void* ws = scratch_on_current_device();
+  if (!ws) return MTS_ERR_HIP;
+  return attention_call("mts_attn_incremental_noalloc launch", cache, layer, q, out, meta, sm_scale, 0.f, ws,
+                        kScratchBytes, stream);
 }
 
 int32_t mts_attn_pointwise(const mts_cache_desc* cache, int32_t layer, const void* q, void* out,
