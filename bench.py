@@ -456,7 +456,10 @@ def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
     stream copies the layer's runs to the onload buffer (hipMemcpyAsync), scatters them
     (mts_kv_unpack) and records an event; the compute stream runs the other users' append +
     attention of that layer, waits for the event, then runs the restored users'.  Serialised: the
-    same calls on one stream, copies first.  Eager launches; PCIe-inclusive."""
+    same calls on one stream, copies first.  Eager launches; PCIe-inclusive.  Consecutive steps are
+    not fenced against each other: in serving, the next batch restores other users into other pages,
+    and the onload buffer's reuse is ordered by the side stream itself (copy after the previous
+    step's scatter of the same layer)."""
     import numpy as np
     import torch
     import paper_2604_22881_amd as mts
@@ -481,7 +484,6 @@ def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
     ws_bytes = max(mts.mts_attn_workspace_bytes(cache.desc, hit_b.meta), mts.mts_attn_workspace_bytes(cache.desc, miss_b.meta))
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     ev = [torch.cuda.Event() for _ in range(L)]
-    ev_start = torch.cuda.Event()
     cs, ss = compute.cuda_stream, side.cuda_stream
 
     def layer_work(l, b, lo, hi):
@@ -490,9 +492,6 @@ def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
 
     def step(overlap):
         xs = ss if overlap else cs
-        if overlap:
-            ev_start.record(compute)
-            side.wait_event(ev_start)                  # the onload buffer is free once the last step is over
         for l in range(L):
             mts.mts_stage_h2d_async(staging[l], pinned[l], layer_bytes, stream=xs)
             mts.mts_kv_unpack(cache.desc, l, staging[l], *segs.args(), miss_b.meta, stream=xs)

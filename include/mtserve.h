@@ -23,7 +23,11 @@
  *     calling thread.
  *   - The kernel entry points may be called from several host threads and may be captured into
  *     a HIP graph.  The first attention call of a process queries the device (occupancy, LDS
- *     limits): make one call outside stream capture before capturing.
+ *     limits): make one call outside stream capture before capturing.  One pattern is known to
+ *     crash a capture on ROCm 7 (host side): making a stream wait, inside the capture, for an
+ *     event that was recorded on that same stream.  mts_xfer_onload_wait_layer issues a
+ *     hipStreamWaitEvent on the caller's stream for an event of the pipeline's own scatter stream,
+ *     which is not part of the caller's capture: it must not be called under stream capture.
  *   - Device-resident metadata (page ids, lengths) cannot be validated on the host.  The
  *     kernels skip any access whose page id is outside [0, num_pages) or whose token lies
  *     beyond the user's page list, so bad metadata gives wrong results, not a fault.
@@ -178,9 +182,27 @@ int32_t mts_kv_append_layers(const mts_cache_desc* cache, int32_t layer_begin, i
                              const mts_batch_meta* meta, void* stream);
 
 /* Workspace mts_attn_incremental needs for this cache and batch shape (host-only, >= 0;
- * < 0 on bad arguments).  The workspace is device memory, 256-byte aligned, and may be
- * reused by later calls on the same stream. */
+ * < 0 on bad arguments).  The workspace is device memory, 256-byte aligned, needs no
+ * initialisation and may be reused by later calls on the same stream (never by calls that
+ * overlap in time). */
 int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_meta* meta);
+
+/*
+ * Tuning and testing override of the attention launch plan.  Process-wide and read by every
+ * attention call and by mts_attn_workspace_bytes: set it before the calls it is meant for, never
+ * while another thread is inside one, and query the workspace size under the same setting as
+ * the call.  A field of 0 keeps the automatic choice; NULL resets everything.  Results are the
+ * same operation under every setting (the parity tests force schedules and kernels with it).
+ */
+enum { MTS_ATTN_KERNEL_AUTO = 0, MTS_ATTN_KERNEL_STREAMING = 1, MTS_ATTN_KERNEL_PREFILL = 2, MTS_ATTN_KERNEL_PLAIN = 3 };
+typedef struct mts_attn_tuning {
+  int32_t min_tiles; /* least kv tiles (32 tokens) of a wavefront's share in the streaming kernel */
+  int32_t max_waves; /* most wavefronts of a streaming launch (multiple of 4, <= 1024) */
+  int32_t pair_cost; /* schedule allowance per (query tile, head), in tiles */
+  int32_t kernel;    /* MTS_ATTN_KERNEL_*: force the split-kv streaming kernel, the dense-prefill kernel
+                        (where it applies) or the plain fp32-accumulate kernel */
+} mts_attn_tuning;
+int32_t mts_attn_set_tuning(const mts_attn_tuning* tuning);
 
 /*
  * Incremental-prefill attention (Sec. 2, Eq. 6-7; Alg. 1 step 8.4).  For user u, head h and
@@ -276,9 +298,10 @@ int32_t mts_attn_pointwise_unappended(const mts_cache_desc* cache, int32_t layer
  * The pool's pages of a staged user are neither read nor written (they must still be allotted
  * in the page table: mts_kv_unpack and the append fill them afterwards).  Served by the
  * streaming bf16 kernel only; MTS_ERR_UNSUPPORTED for fp32 caches and for the long new segments
- * the dense-prefill kernel serves (there, unpack first).  Rows of the onload buffer are read
- * element-wise for V (a transpose by addressing), several times slower per token than pool
- * tiles: meant for the few restored users of a batch.
+ * the dense-prefill kernel serves (there, unpack first).  Rows of the onload buffer are loaded
+ * 16 bytes per lane like pool tiles, V being transposed through LDS on the way, but only two
+ * such tiles are in flight per wavefront: per token they stream about a third more slowly than
+ * pool tiles, which is fine for the few restored users of a batch.
  */
 int32_t mts_attn_incremental_staged(const mts_cache_desc* cache, int32_t layer, const void* q,
                                     const void* k_new, const void* v_new, const void* staged_rows,

@@ -21,7 +21,7 @@ MTS_F32, MTS_BF16 = 0, 1
 EXPORTS = (
     "mts_page_bytes", "mts_pages_for", "mts_elem_offset", "mts_kv_unpack", "mts_kv_pack",
     "mts_kv_unpack_layers", "mts_kv_pack_layers", "mts_kv_append_layers",
-    "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_incremental", "mts_attn_incremental_noalloc", "mts_attn_pointwise",
+    "mts_kv_append", "mts_attn_workspace_bytes", "mts_attn_set_tuning", "mts_attn_incremental", "mts_attn_incremental_noalloc", "mts_attn_pointwise",
     "mts_attn_unappended_appends", "mts_attn_incremental_unappended", "mts_attn_pointwise_unappended",
     "mts_attn_incremental_staged",
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_diag_stream_read", "mts_last_error", "mts_version",
@@ -48,6 +48,13 @@ class BatchMeta(C.Structure):
     _fields_ = [("batch", C.c_int32), ("page_indptr", C.c_void_p), ("page_indices", C.c_void_p),
                 ("prefix_lens", C.c_void_p), ("new_indptr", C.c_void_p), ("total_new", C.c_int32),
                 ("max_new", C.c_int32), ("max_total_len", C.c_int32), ("total_pages", C.c_int32)]
+
+
+class AttnTuning(C.Structure):
+    _fields_ = [("min_tiles", C.c_int32), ("max_waves", C.c_int32), ("pair_cost", C.c_int32), ("kernel", C.c_int32)]
+
+
+MTS_ATTN_KERNEL_AUTO, MTS_ATTN_KERNEL_STREAMING, MTS_ATTN_KERNEL_PREFILL, MTS_ATTN_KERNEL_PLAIN = 0, 1, 2, 3
 
 
 class XferConfig(C.Structure):
@@ -92,6 +99,7 @@ def lib():
         "mts_kv_append": (I32, [DESC, I32, P, P, META, P]),
         "mts_kv_append_layers": (I32, [DESC, I32, I32, P, P, I64, META, P]),
         "mts_attn_workspace_bytes": (I64, [DESC, META]),
+        "mts_attn_set_tuning": (I32, [C.POINTER(AttnTuning)]),
         "mts_attn_incremental": (I32, [DESC, I32, P, P, META, F32, P, I64, P]),
         "mts_attn_incremental_noalloc": (I32, [DESC, I32, P, P, META, F32, P]),
         "mts_attn_pointwise": (I32, [DESC, I32, P, P, META, F32, F32, P, I64, P]),
@@ -181,7 +189,14 @@ def mts_attn_workspace_bytes(desc: CacheDesc, meta: BatchMeta):
     return _check(lib().mts_attn_workspace_bytes(C.byref(desc), C.byref(meta)))
 
 
+def mts_attn_set_tuning(min_tiles=0, max_waves=0, pair_cost=0, kernel=0):
+    """Process-wide override of the attention launch plan; all zeros (the default) resets it."""
+    t = AttnTuning(int(min_tiles), int(max_waves), int(pair_cost), int(kernel))
+    return _check(lib().mts_attn_set_tuning(C.byref(t)))
+
+
 # ---- device entry points ----------------------------------------------------------------
+
 def mts_kv_unpack(desc, layer, staging, num_segs, seg_user, seg_pos, seg_tok_indptr, max_seg_tokens,
                   meta, stream=None):
     return _check(lib().mts_kv_unpack(C.byref(desc), layer, _ptr(staging), num_segs, _ptr(seg_user),

@@ -28,7 +28,7 @@ def sources():
 
 
 def _newest_header() -> float:
-    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hpp", ".inc"))]
     hdrs.append(os.path.join(PKG_DIR, "..", "include", "mtserve.h"))
     return max(os.path.getmtime(h) for h in hdrs)
 
@@ -49,7 +49,7 @@ def _compile(src: str, incremental: bool = False) -> str:
     return obj
 
 
-def build_library(jobs: int = 4, incremental: bool = False) -> str:
+def build_library(jobs: int = 8, incremental: bool = False) -> str:
     """Compiles every source (with `incremental`, only those newer than their object) and links."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "../../include/mtserve.h"
@@ -161,9 +162,13 @@ int32_t set_error(int32_t code, const char* fmt, ...) {
   return code;
 }
 
+// mts_attn_set_tuning: 0 = automatic
+std::atomic<int> g_tune_min_tiles{0}, g_tune_max_waves{0}, g_tune_pair_cost{0}, g_tune_kernel{0};
+
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   AttnPlan p{};
-  p.use_mfma = (g.es == 2);
+  const int force = g_tune_kernel.load(std::memory_order_relaxed);
+  p.use_mfma = (g.es == 2) && force != MTS_ATTN_KERNEL_PLAIN;
   p.q_tile = 16; p.q_tiles_max = 1; p.n_items = 0; p.min_tiles = 4; p.max_waves = 4;
   if (!p.use_mfma || b.total_new <= 0 || b.batch <= 0) return p;
   const int max_new = b.max_new > 0 ? b.max_new : 1;
@@ -171,7 +176,8 @@ AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   // workgroup-per-query-block kernel shares K/V tiles through LDS and needs no workspace.
   // Short ones with long prefixes need the split-kv schedule of the streaming kernel.
   bool prefill = max_new >= 256 && (int64_t)b.total_new >= 128ll * b.batch;
-  if (const char* env = getenv("MTS_ATTN_PREFILL")) prefill = atoi(env) != 0;
+  if (force == MTS_ATTN_KERNEL_PREFILL) prefill = true;
+  if (force == MTS_ATTN_KERNEL_STREAMING) prefill = false;
   if (prefill && attn_prefill_applicable(g, b)) { p.use_prefill = true; return p; }
   p.q_tile = roundup(max_new, 16) < 64 ? roundup(max_new, 16) : 64;
   p.q_tiles_max = (max_new + p.q_tile - 1) / p.q_tile;
@@ -180,20 +186,20 @@ AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b) {
   // tiles; measured optimum 6-12 tiles on three workloads (a flat one), worth 7 % of the launch
   // where a share holds several short pairs and 1-2 % where pairs are longer than shares.
   p.pair_cost = 8;
-  if (const char* env = getenv("MTS_ATTN_PAIR_COST")) { const int v = atoi(env); if (v >= 0 && v <= 64) p.pair_cost = v; }
+  if (const int v = g_tune_pair_cost.load(std::memory_order_relaxed); v > 0) p.pair_cost = v < 64 ? v : 64;
   const int64_t tiles_upper = items * ((b.max_total_len + 31) / 32 + 1 + p.pair_cost) * g.H;   // schedule units of the call
   if (items > 16384 || b.batch > 4096 || tiles_upper >= (1ll << 31)) { p.too_large = true; return p; }
   p.n_items = (int)items;
   // a wavefront's share is never shorter than this: below it, start-up and the partial
   // accumulators cost more than the share itself
-  if (const char* env = getenv("MTS_ATTN_MIN_TILES")) { const int v = atoi(env); if (v >= 1) p.min_tiles = v; }
+  if (const int v = g_tune_min_tiles.load(std::memory_order_relaxed); v >= 1) p.min_tiles = v;
   int64_t waves = (tiles_upper + p.min_tiles - 1) / p.min_tiles;
   waves = (waves + 3) / 4 * 4;
   // 256 CUs x 4 SIMDs: one wavefront per SIMD.  A second one (the kernel is compiled to fit two)
   // measured 2-5 % slower on every shape tried, small or large: it doubles the cuts, and the
   // wavefront that starts second on a SIMD streams more slowly than the first.
-  int64_t cap = 1024;
-  if (const char* env = getenv("MTS_ATTN_MAX_WAVES")) { const int v = atoi(env); if (v >= 4) cap = v / 4 * 4; }
+  int64_t cap = kAttnMaxWaves;
+  if (const int v = g_tune_max_waves.load(std::memory_order_relaxed); v >= 4 && v < cap) cap = v / 4 * 4;
   p.max_waves = (int)(waves < cap ? waves : cap);
   if (p.max_waves < 4) p.max_waves = 4;
   p.ws_desc_bytes = roundup((int64_t)p.max_waves * 32, 256);
@@ -343,6 +349,18 @@ int32_t mts_kv_append_layers(const mts_cache_desc* cache, int32_t layer_begin, i
                     "mts_kv_append_layers launch");
 }
 
+int32_t mts_attn_set_tuning(const mts_attn_tuning* t) {
+  const mts_attn_tuning none{0, 0, 0, 0};
+  if (!t) t = &none;
+  if (t->min_tiles < 0 || t->max_waves < 0 || t->pair_cost < 0 || t->kernel < 0 || t->kernel > MTS_ATTN_KERNEL_PLAIN)
+    return fail(MTS_ERR_INVALID_ARG, "tuning fields must be >= 0 and kernel one of MTS_ATTN_KERNEL_*");
+  mts::g_tune_min_tiles.store(t->min_tiles, std::memory_order_relaxed);
+  mts::g_tune_max_waves.store(t->max_waves, std::memory_order_relaxed);
+  mts::g_tune_pair_cost.store(t->pair_cost, std::memory_order_relaxed);
+  mts::g_tune_kernel.store(t->kernel, std::memory_order_relaxed);
+  return MTS_OK;
+}
+
 int64_t mts_attn_workspace_bytes(const mts_cache_desc* cache, const mts_batch_meta* meta) {
   mts::PoolGeom g{};
   mts::BatchDev b{};
@@ -398,8 +416,7 @@ int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t la
   }
   const float scale = sm_scale > 0.f ? sm_scale : 1.0f / sqrtf((float)g.D);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool plain = getenv("MTS_ATTN_PLAIN") != nullptr;
-  if (plan.use_mfma && !plan.use_prefill && !plain && !(unappended && !rows_fit_32bit(g, b)))
+  if (plan.use_mfma && !plan.use_prefill && !(unappended && !rows_fit_32bit(g, b)))
     return hip_status(mts::launch_attn_mfma(g, plan, q, out, b, scale, inv_norm, plan.ws_bytes > 0 ? workspace : nullptr, s,
                                             unappended ? k_new : nullptr, unappended ? v_new : nullptr, hist), name);
   if (hist)
@@ -412,7 +429,7 @@ int32_t attention_call(const char* name, const mts_cache_desc* cache, int32_t la
     const hipError_t e = mts::launch_append(g, k_new, v_new, b, s);
     if (e != hipSuccess) return hip_status(e, name);
   }
-  if (plan.use_mfma && plan.use_prefill && !plain)
+  if (plan.use_mfma && plan.use_prefill)
     return hip_status(mts::launch_attn_prefill(g, q, out, b, scale, inv_norm, s), name);
   return hip_status(mts::launch_attn_generic(g, q, out, b, scale, inv_norm, s), name);
 }
@@ -466,7 +483,7 @@ int32_t mts_attn_unappended_appends(const mts_cache_desc* cache, const mts_batch
   if ((st = check_meta(meta, true, false, &b)) != MTS_OK) return st;
   if (b.batch == 0 || b.total_new == 0) return 0;
   const mts::AttnPlan plan = mts::plan_attention(g, b);
-  return (plan.use_mfma && !plan.use_prefill && !getenv("MTS_ATTN_PLAIN") && rows_fit_32bit(g, b)) ? 0 : 1;
+  return (plan.use_mfma && !plan.use_prefill && rows_fit_32bit(g, b)) ? 0 : 1;
 }
 
 int32_t mts_attn_incremental_unappended(const mts_cache_desc* cache, int32_t layer, const void* q, const void* k_new,

@@ -23,6 +23,7 @@
 // max, no denominator, no redo; hidden keys carry logit 0 (silu(0) = 0).
 #include <math.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "mts_internal.hpp"
@@ -354,9 +355,18 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
     if constexpr (PW) break;                                     // no statistics, nothing to redo
     // A reference far below the true max shows up as an overflowed (or NaN) denominator of a
     // real query; then every wavefront of the block goes round again.
+    // (the numerator overflows first when the values are large: the sum of a query's absolute
+    // accumulator values is infinite or NaN as soon as one of them is)
     bool bad = false;
 #pragma unroll
-    for (int qb = 0; qb < kNQB; ++qb) bad |= (16 * qb + r < nq) && !(lacc[qb][0] < 1e37f);
+    for (int qb = 0; qb < kNQB; ++qb) {
+      float mag = 0.f;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mag += fabsf(o[db][qb][k]);
+      bad |= (16 * qb + r < nq) && (!(lacc[qb][0] < 1e37f) || !(mag < 3.0e38f));
+    }
     if (tid == 0) redo_flag = 0;
     __syncthreads();
     if (bad) redo_flag = 1;
@@ -390,13 +400,13 @@ hipError_t launch_one(const PoolGeom& g, const BatchDev& b, const uint16_t* q, u
   constexpr int kBlockQ = 64 * NQB;
   int q_blocks_max = (b.max_new + kBlockQ - 1) / kBlockQ;
   if (q_blocks_max < 1) q_blocks_max = 1;
-  static bool attr_set = false;                                  // static + dynamic LDS may pass 64 KiB
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxIdBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::once_flag attr_once;                               // static + dynamic LDS may pass 64 KiB
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(attr_once, [&] {
+    attr_status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kMaxIdBytes);
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const int n_pairs = b.batch * g.H;
   const int64_t grid = (int64_t)((n_pairs + kXcds - 1) / kXcds) * kXcds * q_blocks_max;
   if (grid <= 0 || grid > 0x7fffffffll) return hipErrorInvalidValue;

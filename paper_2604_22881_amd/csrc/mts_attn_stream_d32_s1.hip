@@ -1,0 +1,5 @@
+// Instantiation unit of the streaming attention kernel: head_dim 32, key/value source 1
+// (0 the pool, 1 the step's rows read from k_new / v_new, 2 also restored prefixes from the onload buffer).
+#define MTS_INST_D 32
+#define MTS_INST_SRC 1
+#include "mts_attn_stream.inc"

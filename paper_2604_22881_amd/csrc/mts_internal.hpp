@@ -58,6 +58,8 @@ struct AttnPlan {
   int64_t ws_bytes;      // whole workspace
 };
 AttnPlan plan_attention(const PoolGeom& g, const BatchDev& b);
+constexpr int kAttnMaxWaves = 1024;   // 256 CUs x 4 SIMDs: one wavefront per SIMD
+
 
 // inv_norm selects the aggregation: 0 = softmax (Sec. 2, Eq. 6-7); > 0 = pointwise,
 // out = inv_norm * sum_j silu(sm_scale * q.k_j) v_j (no softmax statistics).

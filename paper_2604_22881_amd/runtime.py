@@ -116,3 +116,4 @@ class HostRuns:
         self.runs = B.XferRuns(segs.num_segs, segs.seg_user.data_ptr(), segs.seg_pos.data_ptr(),
                                segs.seg_tok_indptr.data_ptr(), segs.max_seg_tokens,
                                self._indptr.ctypes.data, C.addressof(ptrs))
+

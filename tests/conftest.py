@@ -27,3 +27,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+# values of mts_attn_tuning.kernel (include/mtserve.h)
+KERNEL_STREAMING, KERNEL_PREFILL, KERNEL_PLAIN = 1, 2, 3
+
+
+@pytest.fixture
+def attn_tuning():
+    """Sets the library's attention tuning override for one test (forced schedules and kernels)
+    and resets it afterwards."""
+    import paper_2604_22881_amd as mts
+
+    def set_(**fields):
+        mts.mts_attn_set_tuning(**fields)
+    yield set_
+    mts.mts_attn_set_tuning()

@@ -35,6 +35,7 @@ class GpuStep:
         self.batch = DeviceBatch.from_workload(w, DEV)
         self.ws_bytes = mts.mts_attn_workspace_bytes(self.cache.desc, self.batch.meta)
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=DEV)
+        self.ws.fill_(0xA5)                              # the workspace needs no initialisation
 
     def unpack_histories(self, data, layer, users=None, chunk=None):
         w = self.w

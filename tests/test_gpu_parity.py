@@ -13,6 +13,8 @@ import mts_workloads as W
 import oracle
 from helpers import draw_step_data, as_values
 
+from conftest import KERNEL_PLAIN, KERNEL_PREFILL, KERNEL_STREAMING  # noqa: F401
+
 pytestmark = pytest.mark.gpu
 
 FILL = 0xFF          # unowned pool bytes: NaN patterns in both element types
@@ -109,23 +111,22 @@ def test_unpack_append_pool_image_and_pack(name):
 SCHEDULES = {
     "default": {},
     # one kv tile per wavefront: every (query tile, head) longer than 32 keys is cut and merged
-    "one_tile_shares": {"MTS_ATTN_MIN_TILES": "1"},
+    "one_tile_shares": {"min_tiles": 1},
     # a single workgroup: each wavefront walks through several (user, head) segments
-    "four_waves": {"MTS_ATTN_MAX_WAVES": "4", "MTS_ATTN_MIN_TILES": "1"},
-    "odd_shares": {"MTS_ATTN_MIN_TILES": "3", "MTS_ATTN_MAX_WAVES": "28"},
+    "four_waves": {"max_waves": 4, "min_tiles": 1},
+    "odd_shares": {"min_tiles": 3, "max_waves": 28},
 }
 
 
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("schedule", list(SCHEDULES))
-def test_attention_small(name, schedule, monkeypatch):
+def test_attention_small(name, schedule, attn_tuning):
     """Element by element against the oracle, under several work schedules: share boundaries
     that cut through (query tile, head)s exercise the partial accumulators and the merge
     kernel; shares that span several users exercise the segment loop."""
     G = _harness()
     w = _case(name)
-    for k, v in SCHEDULES[schedule].items():
-        monkeypatch.setenv(k, v)
+    attn_tuning(**SCHEDULES[schedule])
     data = draw_step_data(w)
     step = G.GpuStep(w, fill_byte=FILL)
     store = _oracle_store(w, data)
@@ -173,15 +174,15 @@ def test_attention_long_new_segments(name):
 
 
 @pytest.mark.parametrize("name", FORCED_PREFILL)
-def test_attention_small_through_the_prefill_kernel(name, monkeypatch):
-    monkeypatch.setenv("MTS_ATTN_PREFILL", "1")
+def test_attention_small_through_the_prefill_kernel(name, attn_tuning):
+    attn_tuning(kernel=KERNEL_PREFILL)
     _attention_matches_oracle(_case(name))
 
 
 @pytest.mark.parametrize("name", ["prefill_d64", "prefill_d128_s32"])
-def test_long_new_segments_through_the_streaming_kernel(name, monkeypatch):
+def test_long_new_segments_through_the_streaming_kernel(name, attn_tuning):
     """The two matrix-core kernels are interchangeable: the same cases with the other one."""
-    monkeypatch.setenv("MTS_ATTN_PREFILL", "0")
+    attn_tuning(kernel=KERNEL_STREAMING)
     dtype, L, H, D, S, prefix, new, chunk = PREFILL_CASES[name]
     _attention_matches_oracle(W.custom_workload(name, 200 + len(name), dtype, L, H, D, S, prefix, new,
                                                 chunk_tokens=chunk))
@@ -208,7 +209,7 @@ def test_tiny_reuse_config_matches_oracle_and_recompute():
         assert np.abs(as_values(got) - full).max() <= 1e-5
 
 
-def test_explicit_scale_and_plain_kernel_agree(monkeypatch):
+def test_explicit_scale_and_plain_kernel_agree(attn_tuning):
     """sm_scale is honoured, and the plain kernel gives the same answer as the MFMA kernel."""
     G = _harness()
     w = _case("bf16_ragged")
@@ -220,7 +221,7 @@ def test_explicit_scale_and_plain_kernel_agree(monkeypatch):
     ref = oracle.attn_incremental(store, 0, data["q"][0], w.page_indptr, w.page_indices,
                                   w.prefix_lens, w.new_indptr, sm_scale=0.3)
     check_attention(w, step.attention(data, 0, sm_scale=0.3), ref)
-    monkeypatch.setenv("MTS_ATTN_PLAIN", "1")
+    attn_tuning(kernel=KERNEL_PLAIN)
     check_attention(w, step.attention(data, 0, sm_scale=0.3), ref)
 
 
@@ -242,14 +243,14 @@ def test_empty_batch_and_no_new_tokens_are_noops():
     assert torch.equal(before, cache.pool)
 
 
-@pytest.mark.parametrize("prefill", [None, "1"])
-def test_late_dominant_key_redoes_the_segment_with_the_exact_max(prefill, monkeypatch):
+@pytest.mark.parametrize("prefill", [None, KERNEL_PREFILL])
+def test_late_dominant_key_redoes_the_segment_with_the_exact_max(prefill, attn_tuning):
     """Both matrix-core kernels (streaming; workgroup-per-query-block, forced on).
     The reference max of a segment is taken from its first tile.  A key far later whose
     logit exceeds it by hundreds overflows the fp32 weights, which the kernel must detect and
     repair by redoing the segment with the exact max: the output is then that key's value row."""
     if prefill is not None:
-        monkeypatch.setenv("MTS_ATTN_PREFILL", prefill)
+        attn_tuning(kernel=prefill)
     G = _harness()
     w = W.custom_workload("dominant", 77, "bf16", 1, 2, 64, 16, [700, 90, 300], [20, 3, 40])
     data = draw_step_data(w)

@@ -11,6 +11,8 @@ import oracle
 from helpers import draw_step_data, as_values
 from test_gpu_parity import CASES, PREFILL_CASES, SCHEDULES, FILL, _case, _oracle_store
 
+from conftest import KERNEL_PLAIN, KERNEL_PREFILL, KERNEL_STREAMING  # noqa: F401
+
 pytestmark = pytest.mark.gpu
 
 
@@ -48,9 +50,8 @@ def _run(w, inv_norm, sm_scale=0.0):
 
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("schedule", list(SCHEDULES))
-def test_pointwise_small(name, schedule, monkeypatch):
-    for k, v in SCHEDULES[schedule].items():
-        monkeypatch.setenv(k, v)
+def test_pointwise_small(name, schedule, attn_tuning):
+    attn_tuning(**SCHEDULES[schedule])
     w = _case(name)
     _run(w, inv_norm=1.0 / max(1, int(w.total_lens.max())))
 
@@ -63,13 +64,13 @@ def test_pointwise_long_new_segments(name):
 
 
 @pytest.mark.parametrize("name", ["bf16_ragged", "bf16_d128_s32", "bf16_empty_users"])
-def test_pointwise_small_through_the_prefill_kernel(name, monkeypatch):
-    monkeypatch.setenv("MTS_ATTN_PREFILL", "1")
+def test_pointwise_small_through_the_prefill_kernel(name, attn_tuning):
+    attn_tuning(kernel=KERNEL_PREFILL)
     _run(_case(name), inv_norm=0.02)
 
 
-def test_pointwise_plain_kernel_agrees(monkeypatch):
-    monkeypatch.setenv("MTS_ATTN_PLAIN", "1")
+def test_pointwise_plain_kernel_agrees(attn_tuning):
+    attn_tuning(kernel=KERNEL_PLAIN)
     _run(_case("bf16_ragged"), inv_norm=0.05, sm_scale=0.2)
 
 

@@ -68,10 +68,9 @@ BF16_CASES = [n for n in CASES if CASES[n][0] == "bf16"]
 
 @pytest.mark.parametrize("name", BF16_CASES)
 @pytest.mark.parametrize("schedule", list(SCHEDULES))
-def test_staged_small(name, schedule, monkeypatch):
+def test_staged_small(name, schedule, attn_tuning):
     """Every second user staged, under every work schedule, runs of 32 tokens (many runs per user)."""
-    for k, v in SCHEDULES[schedule].items():
-        monkeypatch.setenv(k, v)
+    attn_tuning(**SCHEDULES[schedule])
     w = _case(name)
     _run(w, list(range(0, w.batch, 2)), 32)
 

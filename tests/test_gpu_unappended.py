@@ -14,6 +14,8 @@ from test_gpu_parity import (CASES, EDGE_CASES, PREFILL_CASES, SCHEDULES, FILL, 
                              check_attention)
 from test_gpu_pointwise import _check as check_pointwise
 
+from conftest import KERNEL_PLAIN, KERNEL_PREFILL, KERNEL_STREAMING  # noqa: F401
+
 pytestmark = pytest.mark.gpu
 
 
@@ -52,17 +54,16 @@ def _run(w, data=None, inv_norm=None, sm_scale=0.0, concurrent_append=False):
 
 @pytest.mark.parametrize("name", list(CASES))
 @pytest.mark.parametrize("schedule", list(SCHEDULES))
-def test_unappended_small(name, schedule, monkeypatch):
+def test_unappended_small(name, schedule, attn_tuning):
     """Every small case under every work schedule: share boundaries fall inside, before and after
     the tiles that mix pool tokens with new rows."""
-    for k, v in SCHEDULES[schedule].items():
-        monkeypatch.setenv(k, v)
+    attn_tuning(**SCHEDULES[schedule])
     _run(_case(name))
 
 
 @pytest.mark.parametrize("name", list(CASES))
-def test_unappended_pointwise_small(name, monkeypatch):
-    monkeypatch.setenv("MTS_ATTN_MIN_TILES", "1")
+def test_unappended_pointwise_small(name, attn_tuning):
+    attn_tuning(min_tiles=1)
     w = _case(name)
     _run(w, inv_norm=1.0 / max(1, int(w.total_lens.max())))
 
@@ -80,15 +81,15 @@ def test_unappended_edge_shapes(name):
 
 
 @pytest.mark.parametrize("name", ["prefill_d64", "prefill_mixed_lengths"])
-@pytest.mark.parametrize("prefill", ["0", None])
-def test_unappended_long_new_segments(name, prefill, monkeypatch):
+@pytest.mark.parametrize("prefill", [KERNEL_STREAMING, None])
+def test_unappended_long_new_segments(name, prefill, attn_tuning):
     """Several query tiles per user through the streaming kernel (later query tiles see the new
     rows of earlier ones), and the same cases as the library routes them by itself (appended by
     the call, then the workgroup-per-query-block kernel)."""
     dtype, L, H, D, S, prefix, new, chunk = PREFILL_CASES[name]
     w = W.custom_workload(name, 200 + len(name), dtype, L, H, D, S, prefix, new, chunk_tokens=chunk)
     if prefill is not None:
-        monkeypatch.setenv("MTS_ATTN_PREFILL", prefill)
+        attn_tuning(kernel=prefill)
         import torch
         import gpu_harness as G
         data = draw_step_data(w)
