@@ -16,7 +16,10 @@ Readings where the paper is silent: a whole user is evicted at a time; users of
 the batch being prepared are never victims; evicting a user whose newest tokens
 were not persisted yet drops those tokens from the cache (its cached length falls
 back to the persisted length); a batch that cannot be placed even after evicting
-every eligible user is refused and leaves the state untouched.
+every eligible user is refused and leaves the state untouched; a prepared batch
+that is abandoned (its step failed before the commit of Alg. 1 step 7) gives back
+the pages that prepare allotted and takes back its request counts, while users
+evicted to make room for it stay evicted.
 
 Written with an ordered dict and lists for clarity, not speed.  Which physical
 page ids a user receives is not modelled (any free page is as good as another):
@@ -77,6 +80,22 @@ class CacheModel:
             counts.append(want)
         self.batch = list(zip(users, new_tokens))
         return prefix, onload, counts
+
+    def abort_batch(self):
+        """The prepared batch will not run: every user goes back to the pages its cached tokens
+        need in the GPU tier (none if it is not there), and the batch's requests are uncounted."""
+        for u, _ in self.batch:
+            t = self.total.get(u, 0)
+            on_gpu = u in self.lru
+            keep = self.pages_for(t) if on_gpu else 0
+            self.free += self.pages.get(u, 0) - keep
+            if keep:
+                self.pages[u] = keep
+            else:
+                self.pages.pop(u, None)
+            key = "cold_requests" if t == 0 else ("gpu_hits" if on_gpu else "host_hits")
+            self.stats[key] -= 1
+        self.batch = None
 
     def _evict(self, v):
         del self.lru[v]

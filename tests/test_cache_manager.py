@@ -47,6 +47,30 @@ def test_model_locked_users_are_skipped_and_host_copy_survives_eviction():
     assert m.take_evicted() == ["C"] and m.stats["host_hits"] == 1 and m.stats["tokens_dropped"] == 3 + 4
 
 
+def test_model_abandoned_batch_hand_worked():
+    """9 pages of 4 tokens.  A (10 tokens, 3 pages) and B (6 tokens, 2 pages) are resident.  A batch
+    {A +5, C +9} takes 1 + 3 pages; abandoning it returns exactly those 4 and un-counts its two
+    requests; a batch that had to evict B first leaves B evicted when it is abandoned."""
+    m = CacheModel(9, 4, 1 << 30)
+    m.prepare_batch(["A"], [10]); m.commit_batch()
+    m.prepare_batch(["B"], [6]); m.commit_batch()
+    assert m.free == 4 and m.stats["cold_requests"] == 2
+    assert m.prepare_batch(["A", "C"], [5, 9]) == ([10, 0], [0, 0], [4, 3])
+    assert m.free == 0 and m.stats["gpu_hits"] == 1 and m.stats["cold_requests"] == 3
+    m.abort_batch()
+    assert m.free == 4 and m.pages == {"A": 3, "B": 2} and list(m.lru) == ["A", "B"]
+    assert m.stats["gpu_hits"] == 0 and m.stats["cold_requests"] == 2 and m.cached_length("A") == 10
+    assert m.cached_length("C") == 0
+    # the same batch again, prepared and committed, behaves as if the abandoned one never happened
+    assert m.prepare_batch(["A", "C"], [5, 9]) == ([10, 0], [0, 0], [4, 3])
+    m.commit_batch()
+    assert m.cached_length("A") == 15 and m.cached_length("C") == 9 and m.free == 0
+    # D needs 2 pages: B (least recent) is evicted for it; abandoning D does not bring B back
+    assert m.prepare_batch(["D"], [8]) == ([0], [0], [2])
+    m.abort_batch()
+    assert m.take_evicted() == ["B"] and m.free == 2 and m.cached_length("B") == 0 and "D" not in m.pages
+
+
 def test_model_page_arithmetic_of_the_paper():
     """App. C.1: 8 users of 40 008 tokens, 32-token pages -> 8 x 1251 = 10 008 pages."""
     m = CacheModel(50968, 32, 1024)
