@@ -435,21 +435,6 @@ def serving_trace_leg(w, compute, n_users=512, batch=16, warm_steps=60, steps=12
 
 
 
-def sub_batch(w, users, dev):
-    """DeviceBatch of a subset of the workload's users (their page lists, lengths and a ragged
-    offset array over their own rows)."""
-    import numpy as np
-    from paper_2604_22881_amd.runtime import DeviceBatch
-    users = [int(u) for u in users]
-    pages = [w.user_pages(u) for u in users]
-    indptr = np.concatenate([[0], np.cumsum([len(p) for p in pages])]).astype(np.int32)
-    indices = np.concatenate(pages).astype(np.int32) if pages else np.zeros(0, np.int32)
-    new = np.asarray([w.new_lens[u] for u in users], dtype=np.int32)
-    new_indptr = np.concatenate([[0], np.cumsum(new)]).astype(np.int32)
-    prefix = np.asarray([w.prefix_lens[u] for u in users], dtype=np.int32)
-    return DeviceBatch(indptr, indices, prefix, new_indptr, dev), int(new_indptr[-1])
-
-
 def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
     """host_staging with the link in the loop (Sec. 4.2, Sec. 4.4, Alg. 1 step 8.3): the restored
     users' histories lie in pinned host memory in host-chunk runs.  Overlapped: per layer, the side
@@ -463,13 +448,13 @@ def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
     import numpy as np
     import torch
     import paper_2604_22881_amd as mts
-    from paper_2604_22881_amd.runtime import SegmentList
+    from paper_2604_22881_amd.runtime import DeviceBatch, SegmentList
     dev = cache.device
     L, H, D = w.layers, w.heads, w.head_dim
     miss = [int(u) for u in w.miss_users if w.prefix_lens[u] > 0]
     hit = [u for u in range(w.batch) if u not in set(miss)]
-    hit_b, n_hit = sub_batch(w, hit, dev)
-    miss_b, n_miss = sub_batch(w, miss, dev)
+    hit_b, n_hit = DeviceBatch.from_workload_users(w, hit, dev)
+    miss_b, n_miss = DeviceBatch.from_workload_users(w, miss, dev)
     segs = SegmentList.for_histories(list(range(len(miss))), [w.prefix_lens[u] for u in miss], w.chunk_tokens, dev)
     layer_elems = segs.total_tokens * 2 * H * D
     layer_bytes = layer_elems * 2
@@ -477,7 +462,7 @@ def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
     pinned.normal_()
     staging = torch.empty(L, layer_elems, dtype=torch.bfloat16, device=dev)
     evict = [int(u) for u in w.evict_users]
-    full_b, _ = sub_batch(w, list(range(w.batch)), dev)
+    full_b, _ = DeviceBatch.from_workload_users(w, list(range(w.batch)), dev)
     evict_segs = SegmentList.for_histories(evict, [w.total_lens[u] for u in evict], w.chunk_tokens, dev)
     offload = torch.empty(L, max(evict_segs.total_tokens, 1) * 2 * H * D, device=dev, dtype=torch.bfloat16)
     off_stride = offload.stride(0) * 2

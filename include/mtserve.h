@@ -435,7 +435,8 @@ int32_t mts_cm_import_history(mts_cm* m, int64_t user, int32_t total_len);
  * brought up from the host tier first (0 if the GPU tier holds the user; total_len otherwise);
  * page_indptr[batch+1] / page_indices = the users' page lists in CSR form, logical order.
  * MTS_ERR_BUSY: even after evicting every eligible victim the batch does not fit; MTS_ERR_SHAPE:
- * page_capacity (entries of page_indices) is too small.  On any error nothing has changed.
+ * page_capacity (entries of page_indices) is too small.  On any error nothing has changed
+ * (users first seen in a failed call are not tracked).
  */
 int32_t mts_cm_prepare_batch(mts_cm* m, const int64_t* users, const int32_t* new_tokens, int32_t batch,
                              int32_t* prefix_lens, int32_t* onload_lens, int32_t* page_indptr,
@@ -443,6 +444,12 @@ int32_t mts_cm_prepare_batch(mts_cm* m, const int64_t* users, const int32_t* new
 /* The prepared batch has run (Alg. 1 step 7): total_len += new_tokens, the users are on the
  * GPU tier and become the most recently used, in batch order. */
 int32_t mts_cm_commit_batch(mts_cm* m);
+/* The prepared batch will not run (the step failed before its commit): every user of it goes
+ * back to the pages its cached tokens need (none for a user that is not on the GPU tier), the
+ * pages prepare had added return to the free pool and the batch's requests are taken out of the
+ * hit / cold counters.  Users that prepare evicted to make room stay evicted.  With no prepared
+ * batch the call does nothing. */
+int32_t mts_cm_abort_batch(mts_cm* m);
 
 /* Offload trigger (Sec. 4.2): users on the GPU tier whose not-yet-persisted tokens amount to
  * at least one host chunk.  Returns how many were written (<= capacity), most recent first:

@@ -27,7 +27,7 @@ EXPORTS = (
     "mts_stage_h2d_async", "mts_stage_d2h_async", "mts_diag_stream_read", "mts_last_error", "mts_version",
     "mts_xfer_create", "mts_xfer_destroy", "mts_xfer_onload_submit", "mts_xfer_onload_wait_layer",
     "mts_xfer_offload_submit", "mts_xfer_offload_pending_tokens", "mts_xfer_drain",
-    "mts_cm_create", "mts_cm_destroy", "mts_cm_import_history", "mts_cm_cached_length", "mts_cm_prepare_batch", "mts_cm_commit_batch",
+    "mts_cm_create", "mts_cm_destroy", "mts_cm_import_history", "mts_cm_cached_length", "mts_cm_prepare_batch", "mts_cm_commit_batch", "mts_cm_abort_batch",
     "mts_cm_offload_due", "mts_cm_offload_done", "mts_cm_set_locked", "mts_cm_take_evicted", "mts_cm_get_stats",
 )
 
@@ -123,6 +123,7 @@ def lib():
         "mts_cm_import_history": (I32, [P, I64, I32]),
         "mts_cm_prepare_batch": (I32, [P, P, P, I32, P, P, P, P, I64]),
         "mts_cm_commit_batch": (I32, [P]),
+        "mts_cm_abort_batch": (I32, [P]),
         "mts_cm_offload_due": (I32, [P, P, P, P, I32]),
         "mts_cm_offload_done": (I32, [P, I64, I32]),
         "mts_cm_set_locked": (I32, [P, I64, I32]),
@@ -361,6 +362,9 @@ class CacheManager:
 
     def commit_batch(self):
         return _check(lib().mts_cm_commit_batch(self._h))
+
+    def abort_batch(self):
+        return _check(lib().mts_cm_abort_batch(self._h))
 
     def offload_due(self, capacity=1024):
         u = np.zeros(capacity, np.int64); p = np.zeros(capacity, np.int32); c = np.zeros(capacity, np.int32)

@@ -122,8 +122,13 @@ int32_t mts_cm_prepare_batch(mts_cm* m, const int64_t* users, const int32_t* new
   // pass 1: validate, mark the batch (its users are never victims), count the pages it needs
   int64_t need = 0;
   std::vector<User*> us(batch);
+  std::vector<User*> created;                    // users first seen in this call: forgotten again if it fails
   auto unmark = [&](int upto) {
     for (int i = 0; i < upto; ++i) us[i]->batch_new = -1;
+    for (User* c : created) {
+      m->users.erase(c->id);
+      delete c;
+    }
   };
   for (int i = 0; i < batch; ++i) {
     if (new_tokens[i] < 0) { unmark(i); return mts::set_error(MTS_ERR_INVALID_ARG, "new_tokens[%d] is negative", i); }
@@ -133,6 +138,7 @@ int32_t mts_cm_prepare_batch(mts_cm* m, const int64_t* users, const int32_t* new
       u = new User;
       u->id = users[i];
       m->users.emplace(users[i], u);
+      created.push_back(u);
     } else {
       u = it->second;
     }
@@ -195,6 +201,24 @@ int32_t mts_cm_commit_batch(mts_cm* m) {
     } else {                          // nothing cached: holds no pages (pages_for(0) == 0)
       u->on_gpu = false;
     }
+  }
+  m->batch.clear();
+  return MTS_OK;
+}
+
+int32_t mts_cm_abort_batch(mts_cm* m) {
+  if (!m) return mts::set_error(MTS_ERR_INVALID_ARG, "manager is NULL");
+  for (User* u : m->batch) {
+    // back to the pages the cached tokens need in the GPU tier; a user that is not there holds none
+    const size_t keep = u->on_gpu ? (size_t)pages_for(u->total_len, m->page_size) : 0;
+    while (u->pages.size() > keep) {
+      m->free_pages.push_back(u->pages.back());
+      u->pages.pop_back();
+    }
+    if (u->total_len == 0) --m->stats.cold_requests;
+    else if (u->on_gpu) --m->stats.gpu_hits;
+    else --m->stats.host_hits;
+    u->batch_new = -1;
   }
   m->batch.clear();
   return MTS_OK;

@@ -65,6 +65,19 @@ class DeviceBatch:
     def from_workload(cls, w, device="cuda:0"):
         return cls(w.page_indptr, w.page_indices, w.prefix_lens, w.new_indptr, device)
 
+    @classmethod
+    def from_workload_users(cls, w, users, device="cuda:0"):
+        """The batch made of a subset of the workload's users, in the order given: their page lists,
+        prefix lengths and a ragged offset array over their own rows.  Returns (batch, rows)."""
+        users = [int(u) for u in users]
+        pages = [w.user_pages(u) for u in users]
+        indptr = np.concatenate([[0], np.cumsum([len(p) for p in pages])]).astype(np.int32)
+        indices = np.concatenate(pages).astype(np.int32) if pages else np.zeros(0, np.int32)
+        new = np.asarray([w.new_lens[u] for u in users], dtype=np.int32)
+        new_indptr = np.concatenate([[0], np.cumsum(new)]).astype(np.int32)
+        prefix = np.asarray([w.prefix_lens[u] for u in users], dtype=np.int32)
+        return cls(indptr, indices, prefix, new_indptr, device), int(new_indptr[-1])
+
 
 class SegmentList:
     """Runs of tokens in a contiguous staging buffer: (user, first pool token, token count)."""

@@ -112,7 +112,11 @@ def test_manager_matches_model_on_random_traces():
                 # no page belongs to two users
                 held = [p for ps in pages_of.values() for p in ps]
                 assert len(held) == len(set(held)) and all(0 <= p < num_pages for p in held)
-                model.commit_batch(); cm.commit_batch()
+                if rng.random() < 0.15:                 # the step fails before its commit
+                    model.abort_batch(); cm.abort_batch()
+                    pages_of = {u: ps[:model.pages.get(u, 0)] for u, ps in pages_of.items() if model.pages.get(u, 0)}
+                else:
+                    model.commit_batch(); cm.commit_batch()
             if step % 7 == 3:
                 due = model.offload_due()
                 u, p, c = cm.offload_due()
@@ -169,6 +173,7 @@ def test_manager_rejects_bad_arguments_and_leaves_state():
         cm.prepare_batch([1], [100])                                      # 25 pages > 8
     assert e.value.code == mts.MTS_ERR_BUSY
     assert cm.stats()["free_pages"] == 8 and cm.cached_length(1) == 0
+    assert cm.stats()["users_tracked"] == 0                               # failed calls track nobody
     p, o, indptr, idx = cm.prepare_batch([1, 2], [5, 0])
     assert p.tolist() == [0, 0] and indptr.tolist() == [0, 2, 2] and len(idx) == 2
     with pytest.raises(mts.MtsError):
@@ -179,6 +184,32 @@ def test_manager_rejects_bad_arguments_and_leaves_state():
         cm.offload_done(77, 1)
     with pytest.raises(mts.MtsError):
         mts.CacheManager(0, 16)
+
+
+def test_manager_abandoned_batch_matches_model():
+    cm = mts.CacheManager(9, 4, 1 << 20)
+    model = CacheModel(9, 4, 1 << 20)
+    for u, n in ((1, 10), (2, 6)):
+        model.prepare_batch([u], [n]); model.commit_batch()
+        cm.prepare_batch([u], [n]); cm.commit_batch()
+    before = cm.prepare_batch([1], [0])[3].tolist(); cm.abort_batch()        # user 1's pages, nothing else changes
+    assert model.prepare_batch([1, 3], [5, 9]) == ([10, 0], [0, 0], [4, 3])
+    prefix, onload, indptr, indices = cm.prepare_batch([1, 3], [5, 9])
+    assert prefix.tolist() == [10, 0] and np.diff(indptr).tolist() == [4, 3] and cm.stats()["free_pages"] == 0
+    assert indices[:3].tolist() == before
+    model.abort_batch(); cm.abort_batch()
+    st = cm.stats()
+    assert st["free_pages"] == model.free == 4 and st["gpu_hits"] == model.stats["gpu_hits"] == 0
+    assert st["cold_requests"] == model.stats["cold_requests"] == 2 and cm.cached_length(3) == 0
+    cm.abort_batch()                                                         # nothing prepared: no-op
+    assert cm.prepare_batch([1], [0])[3].tolist() == before                  # user 1 kept its first three pages
+    cm.commit_batch()
+    # evictions made for an abandoned batch stay
+    model.prepare_batch([1], [0]); model.commit_batch()
+    assert model.prepare_batch([4], [24]) is not None and cm.prepare_batch([4], [24]) is not None   # 6 pages: evicts 2
+    model.abort_batch(); cm.abort_batch()
+    assert cm.take_evicted().tolist() == model.take_evicted() == [2]
+    assert cm.stats()["free_pages"] == model.free == 6 and cm.cached_length(2) == 0
 
 
 def test_hit_ratios_on_heavy_tailed_arrivals():

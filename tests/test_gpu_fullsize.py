@@ -42,10 +42,31 @@ def _sample_users(w, rng, count):
 @pytest.mark.parametrize("name,n_users,n_heads", [("batched_incremental", 8, 3), ("long_history", 4, 2),
                                                   ("host_staging", 6, 2), ("miss_prefill", 2, 2)])
 def test_sampled_pairs_match_oracle(name, n_users, n_heads, unappended):
+    _pairs_match_oracle(name, n_users, n_heads, unappended, pointwise=False)
+
+
+@pytest.mark.parametrize("name,n_users,n_heads", [("batched_incremental", 8, 3), ("long_history", 4, 2),
+                                                  ("host_staging", 6, 2), ("miss_prefill", 2, 2)])
+def test_sampled_pairs_match_oracle_pointwise(name, n_users, n_heads):
+    """mts_attn_pointwise at the full sizes, same sampling (definition of the aggregation: the header's)."""
+    _pairs_match_oracle(name, n_users, n_heads, False, pointwise=True)
+
+
+@pytest.mark.parametrize("name,n_users", [("batched_incremental", 64), ("long_history", 32), ("host_staging", 256),
+                                          ("miss_prefill", 3)])
+def test_every_head_of_many_users_matches_oracle(name, n_users):
+    """The same comparison on every head of all users (three users of miss_prefill): a wrong key,
+    weight or page anywhere in those rows shows, which the unit-value property below cannot see."""
+    _pairs_match_oracle(name, n_users, None, False, pointwise=False)
+
+
+def _pairs_match_oracle(name, n_users, n_heads, unappended, pointwise):
     torch, G, w, step = _setup(name)
     rng = np.random.default_rng([w.seed, 5])
     users = _sample_users(w, rng, n_users)
-    heads = sorted(rng.choice(w.heads, size=n_heads, replace=False).tolist())
+    heads = (list(range(w.heads)) if n_heads is None else
+             sorted(rng.choice(w.heads, size=n_heads, replace=False).tolist()))
+    inv_norm = 1.0 / max(1, int(w.total_lens.max()))
     H, D = w.heads, w.head_dim
     # seeded host data for the sampled users only; everybody else keeps the device-side draw
     data = {"layers": [0], "hist": {0: [None] * w.batch}}
@@ -64,15 +85,19 @@ def test_sampled_pairs_match_oracle(name, n_users, n_heads, unappended):
         torch.cuda.synchronize()
     else:
         step.append(data, 0)
-        got = step.attention(data, 0)
+        got = step.attention_pointwise(data, 0, inv_norm) if pointwise else step.attention(data, 0)
     for u in users:
         pages = w.user_pages(u)
         for start, cnt in W.host_chunks(int(w.prefix_lens[u]), w.chunk_tokens):
             oracle.unpack(store, 0, data["hist"][0][u][:, start:start + cnt], pages, start)
     oracle.append(store, 0, data["k_new"][0], data["v_new"][0], w.page_indptr, w.page_indices,
                   w.prefix_lens, w.new_indptr)
-    ref = oracle.attn_incremental(store, 0, data["q"][0], w.page_indptr, w.page_indices,
-                                  w.prefix_lens, w.new_indptr, users=users, heads=heads)
+    if pointwise:
+        ref = oracle.attn_pointwise(store, 0, data["q"][0], w.page_indptr, w.page_indices,
+                                    w.prefix_lens, w.new_indptr, inv_norm, users=users, heads=heads)
+    else:
+        ref = oracle.attn_incremental(store, 0, data["q"][0], w.page_indptr, w.page_indices,
+                                      w.prefix_lens, w.new_indptr, users=users, heads=heads)
     gv = as_values(got)
     assert np.isfinite(gv).all()
     worst = 0.0

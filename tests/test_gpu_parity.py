@@ -277,6 +277,45 @@ def test_late_dominant_key_redoes_the_segment_with_the_exact_max(prefill, attn_t
     assert np.allclose(ref[lo:hi, 0], as_values(data["hist"][0][0][1, 555, 0]), atol=1e-6)
 
 
+@pytest.mark.parametrize("schedule", ["default", "one_tile_shares"])
+@pytest.mark.parametrize("prefill", [None, KERNEL_PREFILL])
+def test_large_values_overflow_the_numerator_before_the_denominator(prefill, schedule, attn_tuning):
+    """Values of magnitude ~100 and one late key whose logit lies 85 nats above the first tile's:
+    against the first tile's reference the softmax denominator stays just below the overflow
+    test (e^85 = 8e36) while weight x value passes the fp32 range.  The kernels must notice the
+    overflowed numerators and redo the segment with the exact max; the oracle (fp64) is finite."""
+    fields = dict(SCHEDULES[schedule])
+    if prefill is not None:
+        fields["kernel"] = prefill
+    attn_tuning(**fields)
+    G = _harness()
+    w = W.custom_workload("big_values", 78, "bf16", 1, 2, 64, 16, [700, 300, 64], [20, 40, 7])
+    data = draw_step_data(w)
+    late = {0: 555, 1: 237, 2: 50}
+    for u, tok in late.items():
+        h = np.array(data["hist"][0][u])
+        h[0] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(h[0]) * 0.01)          # logits ~ 0 everywhere ...
+        h[0, tok] = W.f32_to_bf16_bits(np.full((w.heads, w.head_dim), 10.625, np.float32))   # ... but here: 85 nats
+        h[1] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(h[1]) * 100.0)         # values ~ N(0, 100^2)
+        data["hist"][0][u] = h
+    data["k_new"][0] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(data["k_new"][0]) * 0.01)
+    data["v_new"][0] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(data["v_new"][0]) * 100.0)
+    data["q"][0] = W.f32_to_bf16_bits(np.ones_like(W.bf16_bits_to_f32(data["q"][0])))   # q.k_late / 8 = 85
+    step = G.GpuStep(w, fill_byte=FILL)
+    store = _oracle_store(w, data)
+    step.unpack_histories(data, 0)
+    step.append(data, 0)
+    got = step.attention(data, 0)
+    ref = oracle.attn_incremental(store, 0, data["q"][0], w.page_indptr, w.page_indices,
+                                  w.prefix_lens, w.new_indptr)
+    assert np.isfinite(as_values(got)).all()
+    check_attention(w, got, ref)
+    # sanity of the construction: the late key takes all the weight, and its values are large
+    lo = int(w.new_indptr[0])
+    assert np.allclose(ref[lo, 0], as_values(data["hist"][0][0][1, 555, 0]), rtol=1e-6)
+    assert np.abs(ref).max() > 100
+
+
 EDGE_CASES = {
     # the largest batch the schedule takes (its metadata fills ~64 KiB of LDS), tiny users
     "batch_4096": lambda rng: ("bf16", 1, 1, 64, 16, rng.integers(0, 40, 4096), rng.integers(0, 4, 4096)),

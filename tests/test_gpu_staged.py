@@ -84,11 +84,41 @@ def test_staged_all_users_long_runs(name):
 @pytest.mark.parametrize("seed", range(16))
 def test_staged_random_shapes(seed):
     w = _random_case(seed)
-    if int(w.new_lens.max()) >= 256 and int(w.total_new) >= 128 * w.batch and w.head_dim in (64, 128):
-        pytest.skip("served by the dense-prefill kernel: histories are unpacked first for this shape")
     rng = np.random.default_rng(seed)
     staged = [u for u in range(w.batch) if rng.random() < 0.5]
-    _run(w, staged, int(rng.choice([32, 64, 256, 1024])))
+    chunk = int(rng.choice([32, 64, 256, 1024]))
+    if int(w.new_lens.max()) >= 256 and int(w.total_new) >= 128 * w.batch and w.head_dim in (64, 128):
+        # long new segments are served by the dense-prefill kernel, which reads the pool only: the
+        # staged call must refuse the shape (histories are unpacked first there), before any launch
+        _refused_as_unsupported(w, chunk)
+        return
+    _run(w, staged, chunk)
+
+
+def _refused_as_unsupported(w, chunk):
+    import torch
+    import gpu_harness as G
+    import paper_2604_22881_amd as mts
+    from paper_2604_22881_amd import binding as B
+    step = G.GpuStep(w, fill_byte=FILL)
+    before = step.pool_image(0)
+    x = torch.zeros(max(w.total_new, 1) * w.heads * w.head_dim + 8, dtype=torch.int16, device=G.DEV)
+    out = torch.full_like(x, 7)
+    first = torch.full((w.batch,), -1, dtype=torch.int32, device=G.DEV)
+    tok = torch.zeros(2, dtype=torch.int64, device=G.DEV)
+    with pytest.raises(mts.MtsError) as e:
+        mts.mts_attn_incremental_staged(step.cache.desc, 0, x, x, x, x, first, tok, chunk, out, step.batch.meta, 0.0,
+                                        step.ws, step.ws_bytes)
+    assert e.value.code == B.MTS_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((out == 7).all()), "the refused call wrote output rows"
+    assert np.array_equal(step.pool_image(0), before), "the refused call touched the pool"
+
+
+def test_staged_prefill_shape_is_refused():
+    """A cache-miss shape (every user hundreds of new tokens) handed to the staged call: MTS_ERR_UNSUPPORTED."""
+    w = W.custom_workload("staged_prefill_shape", 92, "bf16", 1, 2, 128, 16, [64, 0, 700], [300, 512, 260])
+    _refused_as_unsupported(w, 64)
 
 
 def test_staged_prefix_lengths_around_run_and_tile_boundaries():
