@@ -490,18 +490,47 @@ def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
         if evict_segs.num_segs:
             mts.mts_kv_pack_layers(cache.desc, 0, L, offload, off_stride, *evict_segs.args(), full_b.meta, stream=cs)
 
-    def timed(overlap):
+    # Sec. 4.1's dual use of the onload buffer: the restored users' attention reads their histories
+    # where the DMA put them (mts_attn_incremental_staged), as soon as a layer has landed; the scatter
+    # of all layers and the restored users' append move behind the layer loop.
+    first_run = np.zeros(len(miss), np.int32)
+    su = segs.seg_user.cpu().numpy()
+    for sidx in range(segs.num_segs - 1, -1, -1):
+        first_run[su[sidx]] = sidx
+    first_run_dev = torch.from_numpy(first_run).to(dev)
+    rows_stride = k_new.stride(0) * k_new.element_size()
+    lo_m, hi_m = n_hit, n_hit + n_miss
+
+    def step_attend_staged(_overlap=True):
+        for l in range(L):
+            mts.mts_stage_h2d_async(staging[l], pinned[l], layer_bytes, stream=ss)
+            ev[l].record(side)
+        for l in range(L):
+            layer_work(l, hit_b, 0, n_hit)
+            compute.wait_event(ev[l])
+            mts.mts_attn_incremental_staged(cache.desc, l, q[l][lo_m:hi_m], k_new[l][lo_m:hi_m], v_new[l][lo_m:hi_m],
+                                            staging[l], first_run_dev, segs.seg_tok_indptr, w.chunk_tokens,
+                                            out[l][lo_m:hi_m], miss_b.meta, 0.0, ws, ws_bytes, stream=cs)
+        mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, layer_bytes, *segs.args(), miss_b.meta, stream=cs)
+        mts.mts_kv_append_layers(cache.desc, 0, L, k_new[0][lo_m:hi_m], v_new[0][lo_m:hi_m], rows_stride, miss_b.meta,
+                                 stream=cs)
+        if evict_segs.num_segs:
+            mts.mts_kv_pack_layers(cache.desc, 0, L, offload, off_stride, *evict_segs.args(), full_b.meta, stream=cs)
+
+    def timed(overlap, fn=None):
+        fn = fn or step
         for _ in range(3):
-            step(overlap)
+            fn(overlap)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            step(overlap)
+            fn(overlap)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
     t_over = timed(True)
     t_ser = timed(False)
+    t_staged = timed(True, step_attend_staged)
     # the transfer alone, in the per-layer pieces the step uses, and as one plain copy of the same bytes
     def copy_only(per_layer):
         torch.cuda.synchronize()
@@ -534,7 +563,8 @@ def pcie_leg(w, cache, q, k_new, v_new, out, compute, side, steps, resident_ms):
     torch.cuda.synchronize()
     t_split = (time.perf_counter() - t0) * 1e3 / steps
     transfer_ms = max(t_ser - t_split, 1e-9)
-    return {"ms_per_step_overlapped": t_over, "ms_per_step_serialised": t_ser,
+    return {"ms_per_step_overlapped": t_over, "ms_per_step_overlapped_attend_from_onload_buffer": t_staged,
+            "ms_per_step_serialised": t_ser,
             "ms_per_step_two_batches_staging_in_hbm": t_split, "ms_per_step_staging_in_hbm_one_batch_graph": resident_ms,
             "h2d_bytes_per_step": L * layer_bytes, "h2d_ms_per_step_alone": t_h2d,
             "h2d_gbps": L * layer_bytes / (t_h2d * 1e-3) / 1e9,
