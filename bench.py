@@ -744,6 +744,40 @@ def bench_workload(args, name, steps, warmup, extras):
         step(attn_ev[s])
     torch.cuda.synchronize()
 
+    # The data-movement kernels of the step, each launch bracketed by HIP events (eager, K more steps):
+    # scatter of the restored histories (Sec. 3.2 step 3), append (Alg. 1 step 8.2), gather of the
+    # offloaded users (Sec. 3.2 step 6).  HBM bytes of a launch = its payload read once and written once.
+    es = 2
+    def timed_launches(fn, n):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:
+            a.record(compute)
+            fn()
+            b.record(compute)
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in evs]
+
+    def movement(payload_bytes, ms):
+        sp = spread(ms)
+        return {"launch_ms": sp, "payload_bytes": int(payload_bytes),
+                "hbm_gbps": 2 * payload_bytes / (sp["median"] * 1e-3) / 1e9,
+                "hbm_frac_of_peak": 2 * payload_bytes / (sp["median"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+    data_movement = {}
+    with torch.cuda.stream(compute):
+        ms = []
+        for l in range(L):
+            ms += timed_launches(lambda: mts.mts_kv_append(cache.desc, l, k_new[l], v_new[l], batch.meta, stream=cs), K)
+        data_movement["mts_kv_append (one layer)"] = movement(2 * N * H * D * es, ms)
+        if miss_segs.num_segs:
+            ms = timed_launches(lambda: mts.mts_kv_unpack_layers(cache.desc, 0, L, staging, staging_stride,
+                                                                 *miss_segs.args(), batch.meta, stream=cs), K)
+            data_movement["mts_kv_unpack_layers (all layers)"] = movement(miss_segs.total_tokens * 2 * H * D * es * L, ms)
+        if evict_segs.num_segs:
+            ms = timed_launches(lambda: mts.mts_kv_pack_layers(cache.desc, 0, L, offload, offload_stride,
+                                                               *evict_segs.args(), batch.meta, stream=cs), K)
+            data_movement["mts_kv_pack_layers (all layers)"] = movement(evict_segs.total_tokens * 2 * H * D * es * L, ms)
+
     if args.calibrate_copy and extras:
         # cal_src was filled before all the work above, so none of it is left in any cache
         cal_dst = torch.empty_like(cal_src)
@@ -772,6 +806,7 @@ def bench_workload(args, name, steps, warmup, extras):
         "kv_read_frac_of_peak_step": kv_bytes * L / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "attention_tflops": flops / (attn_ms_avg * 1e-3) / 1e12,
         "attention_launch_ms": spread(attn_ms),
+        "data_movement": data_movement,
         "roofline": {"kernel": ("mts_attn_pointwise" if pointwise else "mts_attn_incremental") +
                                ("_unappended" if deferred_append else "") + " (one launch = one layer of the batch)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
