@@ -72,6 +72,9 @@ def parse():
                          "too (Alg. 1 steps 8.3 and 9)")
     ap.add_argument("--no-miss", action="store_true", help="diagnostic: no restored users (no unpack, no per-layer wait)")
     ap.add_argument("--no-evict", action="store_true", help="diagnostic: no packed users")
+    ap.add_argument("--page-size", type=int, default=16, choices=(16, 32, 64),
+                    help="tokens per page of the pool (the BASELINE shapes use 16; the paper's default "
+                         "cache configuration is 32)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, as the known-size yardstick for HBM counters")
     return ap.parse_args()
@@ -585,7 +588,7 @@ def bench_workload(args, name, steps, warmup, extras):
     from paper_2604_22881_amd.runtime import DeviceBatch, PagedKVCache, SegmentList
 
     dev = "cuda:0"
-    w = W.make_workload(name)
+    w = W.with_page_size(W.make_workload(name), args.page_size)
     assert w.dtype == "bf16", "the benchmark workloads are bf16"
     L, H, D = w.layers, w.heads, w.head_dim
     torch.manual_seed(w.seed)

@@ -182,6 +182,16 @@ def make_workload(name: str, seed: int | None = None) -> Workload:
     return w
 
 
+def with_page_size(w: Workload, page_size: int) -> Workload:
+    """The same users, lengths and roles with the pool cut into pages of another size (block
+    tables redrawn from the workload's seed)."""
+    if page_size == w.page_size:
+        return w
+    return custom_workload(w.name, w.seed, w.dtype, w.layers, w.heads, w.head_dim, page_size,
+                           w.prefix_lens, w.new_lens, miss_users=w.miss_users, evict_users=w.evict_users,
+                           chunk_tokens=w.chunk_tokens)
+
+
 def host_chunks(length: int, chunk_tokens: int):
     """Token ranges [(start, count), ...] of a history kept on the host in
     fixed-size chunks (Sec. 4.1, CPU tier); the last chunk may be short."""

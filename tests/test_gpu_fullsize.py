@@ -20,10 +20,12 @@ from helpers import as_values
 pytestmark = pytest.mark.gpu
 
 
-def _setup(name):
+def _setup(name, page_size=None):
     import torch
     import gpu_harness as G
     w = dataclasses.replace(W.make_workload(name), layers=1)     # one layer of the workload
+    if page_size is not None:
+        w = W.with_page_size(w, page_size)
     step = G.GpuStep(w, fill_byte=None)
     torch.manual_seed(w.seed)
     step.cache.pool.view(torch.bfloat16).normal_()               # all users: N(0,1) K/V
@@ -60,8 +62,16 @@ def test_every_head_of_many_users_matches_oracle(name, n_users):
     _pairs_match_oracle(name, n_users, None, False, pointwise=False)
 
 
-def _pairs_match_oracle(name, n_users, n_heads, unappended, pointwise):
-    torch, G, w, step = _setup(name)
+@pytest.mark.parametrize("name,n_users,n_heads,page_size", [("long_history", 4, 2, 32), ("batched_incremental", 8, 3, 32),
+                                                            ("host_staging", 6, 2, 64), ("miss_prefill", 2, 2, 32)])
+def test_sampled_pairs_match_oracle_at_other_page_sizes(name, n_users, n_heads, page_size):
+    """The benchmark shapes with the pool cut into 32-token pages (the paper's default, Sec. 5.1)
+    and 64-token pages instead of 16."""
+    _pairs_match_oracle(name, n_users, n_heads, False, pointwise=False, page_size=page_size)
+
+
+def _pairs_match_oracle(name, n_users, n_heads, unappended, pointwise, page_size=None):
+    torch, G, w, step = _setup(name, page_size)
     rng = np.random.default_rng([w.seed, 5])
     users = _sample_users(w, rng, n_users)
     heads = (list(range(w.heads)) if n_heads is None else
