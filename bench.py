@@ -869,8 +869,8 @@ def main():
         # the other BASELINE shapes, each with its own step time and roofline
         res["configs"] = {}
         for name in OTHERS:
-            k = max(10, min(args.steps, 50 if name != "miss_prefill" else 20))
-            r = bench_workload(args, name, k, max(2, min(args.warmup, 5)), extras=False)
+            k = max(10, min(args.steps, 50))             # >= 10 warm-up and 50 timed steps at the defaults
+            r = bench_workload(args, name, k, max(2, min(args.warmup, 10)), extras=False)
             res["configs"][name] = r
     res["hbm_read_ceiling"] = read_ceiling("cuda:0", mts, torch, compute)
     if not args.no_cpu_baseline:
