@@ -269,7 +269,9 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
   auto step = [&](auto masked_c, auto slot_c, int tile) __attribute__((always_inline)) {
     constexpr int pn = (decltype(slot_c)::value + 1) % PFD;
     const int st = tile & 1;
-    compute(masked_c, st, tile);
+    // tiles past the wavefront's own last query hold no key it may see (the later wavefronts of
+    // the block still need them): it only helps to move them
+    if (!decltype(masked_c)::value || tile < tiles_w) compute(masked_c, st, tile);
     park(std::integral_constant<int, pn>{}, st ^ 1);
     load(std::integral_constant<int, pn>{}, tile + 1 + PFD);
     __syncthreads();
