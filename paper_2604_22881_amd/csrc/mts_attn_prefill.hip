@@ -243,7 +243,8 @@ __global__ __launch_bounds__(256, WPS) void attn_prefill_kernel(PoolGeom g, Batc
   };
   // One tile from LDS stage st for all four query blocks, with no branch between them.  Query
   // blocks past the segment's end hold zero queries and are never written; a wavefront whose
-  // queries all lie before the tile computes weights of exactly zero.  MASKED adds what only
+  // queries all lie before the tile would compute weights of exactly zero (step() skips those
+  // tiles in the causal tail).  MASKED adds what only
   // the causal tail needs: the mask, and zeroing of V slots past the user's last token (they
   // may hold anything).
   auto compute = [&](auto masked_c, int st, int tile) __attribute__((always_inline)) {
